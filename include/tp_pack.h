@@ -1,0 +1,159 @@
+/*
+ * tp_pack.h - C ABI of the MI355X strided-datatype pack/unpack library.
+ *
+ * The library implements the datatype-handling path of the TEMPI paper
+ * (arXiv 2012.14363) for one AMD CDNA4 GPU:
+ *
+ *   constructors (Sec. 2)  ->  commit: translate to the Type IR (Sec. 3.1),
+ *   canonicalize by dense folding / stream elision / stream flattening
+ *   (Sec. 3.2, Alg. 1-4), convert to one StridedBlock (Sec. 3.3, Alg. 5) and
+ *   plan the kernel (Sec. 3.3)  ->  MPI_Pack / MPI_Unpack on GPU buffers
+ *   (Sec. 6.2), optionally with the contiguous side in pinned host memory
+ *   (the pack half of the "one-shot" method, Sec. 4).
+ *
+ * Conventions
+ *   - Every function returns TP_SUCCESS (0) or a positive TP_ERR_* code.  On
+ *     any error the out-parameters (*newtype, *position, *size, ...) are left
+ *     unchanged and no data is written.  Nothing throws, nothing aborts.
+ *   - All displacements, sizes and extents are bytes in int64_t.
+ *   - Handles are small integers owned by the library until tp_type_free.  A
+ *     derived type keeps its own reference to its oldtype, so freeing the
+ *     oldtype right after construction is legal (as in MPI).
+ *   - The caller owns every data buffer.  The library allocates no device
+ *     memory and keeps no per-type metadata on the device: everything a kernel
+ *     needs travels in its kernel arguments (Sec. 3.3, last paragraph).
+ *   - Thread safety: the handle table is guarded by a mutex; pack/unpack calls
+ *     may run concurrently on distinct streams.
+ *   - There is no CPU fallback: pack/unpack need a working HIP device and
+ *     return TP_ERR_OTHER without one.
+ */
+#ifndef TP_PACK_H
+#define TP_PACK_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t tp_type; /* opaque datatype handle; negative values are never valid */
+
+#define TP_TYPE_NULL ((tp_type)-1)
+
+/* Predefined (named) types, Sec. 2 first bullet.  Always valid and committed. */
+#define TP_BYTE   ((tp_type)0)
+#define TP_CHAR   ((tp_type)1)
+#define TP_INT8   ((tp_type)2)
+#define TP_UINT8  ((tp_type)3)
+#define TP_INT16  ((tp_type)4)
+#define TP_UINT16 ((tp_type)5)
+#define TP_INT32  ((tp_type)6)
+#define TP_UINT32 ((tp_type)7)
+#define TP_INT64  ((tp_type)8)
+#define TP_UINT64 ((tp_type)9)
+#define TP_FLOAT  ((tp_type)10)
+#define TP_DOUBLE ((tp_type)11)
+#define TP_NUM_PREDEFINED 12
+
+#define TP_ORDER_C 0
+#define TP_ORDER_FORTRAN 1
+
+#define TP_MAX_DIMS 16 /* most dimensions a StridedBlock (or a subarray) may have */
+
+enum {
+    TP_SUCCESS = 0,
+    TP_ERR_TYPE = 1,     /* invalid or freed handle; or type not committed at pack/unpack time       */
+    TP_ERR_COUNT = 2,    /* negative count / blocklength / incount / outcount                         */
+    TP_ERR_ARG = 3,      /* null out-pointer, ndims out of [1, TP_MAX_DIMS], bad subarray box, bad order,
+                            negative position or buffer size, unknown override key                    */
+    TP_ERR_TRUNCATE = 4, /* *position + count*size exceeds the contiguous buffer's size               */
+    TP_ERR_BUFFER = 5,   /* null data pointer with bytes to move, or memory the GPU cannot address    */
+    TP_ERR_OTHER = 6,    /* HIP runtime failure (no device, launch error); see tp_error_string        */
+    TP_ERR_RANGE = 7     /* a size, extent or canonical form overflows int64 or exceeds TP_MAX_DIMS   */
+};
+
+/* ---- constructors (Sec. 2: contiguous, vector/hvector, subarray) -------------------------------
+ * Each stores a new handle in *newtype.  `old` may be any valid handle, committed or not.
+ * Counts and blocklengths must be >= 0 (0 gives an empty type); strides may be negative.
+ *
+ * tp_type_contiguous:      `count` copies of old, each extent(old) bytes after the previous one.
+ * tp_type_vector:          `count` blocks of `blocklength` copies of old; block starts are
+ *                          `stride` * extent(old) bytes apart.
+ * tp_type_create_hvector:  the same with the block stride given in bytes.
+ * tp_type_create_subarray: the `subsizes` box at `starts` of an ndims-dimensional array of `sizes`
+ *                          elements of old.  TP_ORDER_C: the last dimension is contiguous;
+ *                          TP_ORDER_FORTRAN: the first.  The new type's lower bound is 0 and its
+ *                          extent that of the whole array.  Requires 0 <= subsizes[i] <= sizes[i],
+ *                          sizes[i] >= 1, 0 <= starts[i] <= sizes[i] - subsizes[i].
+ * Extent of every type is ub - lb with no alignment padding.
+ */
+int tp_type_contiguous(int count, tp_type old, tp_type *newtype);
+int tp_type_vector(int count, int blocklength, int stride, tp_type old, tp_type *newtype);
+int tp_type_create_hvector(int count, int blocklength, int64_t stride_bytes, tp_type old, tp_type *newtype);
+int tp_type_create_subarray(int ndims, const int sizes[], const int subsizes[], const int starts[], int order,
+                            tp_type old, tp_type *newtype);
+
+/* tp_type_commit: Sec. 3 - translate, canonicalize, convert to a StridedBlock and cache the
+ * kernel plan inside the handle.  Idempotent; host only; *t is not modified.
+ * tp_type_free: drops the caller's reference and sets *t = TP_TYPE_NULL.  Predefined types
+ * cannot be freed (TP_ERR_TYPE). */
+int tp_type_commit(tp_type *t);
+int tp_type_free(tp_type *t);
+
+/* Size (data bytes of one object), lower bound and extent; pack size of `incount` objects
+ * (= incount * size: the packed stream has no header). */
+int tp_type_size(tp_type t, int64_t *size);
+int tp_type_get_extent(tp_type t, int64_t *lb, int64_t *extent);
+int tp_pack_size(int incount, tp_type t, int64_t *size);
+
+/* ---- pack / unpack (MPI_Pack / MPI_Unpack semantics, Sec. 6.2) ---------------------------------
+ * tp_pack:   object i (0 <= i < incount) has its origin at inbuf + i*extent; its bytes, in
+ *            type-map order, go to outbuf + *position onward.  Requires
+ *            0 <= *position and *position + incount*size <= outsize, else TP_ERR_TRUNCATE.
+ *            On success *position += incount*size.
+ * tp_unpack: the mirror: reads inbuf + *position onward (insize = bytes in inbuf), writes
+ *            outcount objects at outbuf + i*extent; bytes of outbuf outside the type map are not
+ *            touched.  Unpacking a type whose map overlaps itself is erroneous (as in MPI):
+ *            which duplicate wins is unspecified.
+ *
+ * Memory: the typed (non-contiguous) buffer - inbuf of pack, outbuf of unpack - must be DEVICE
+ * memory.  The contiguous buffer may be device memory or pinned, GPU-mapped host memory
+ * (hipHostMalloc): the latter is the zero-copy path of Sec. 4.  Pageable host memory gives
+ * TP_ERR_BUFFER.  `hip_stream` is a hipStream_t (NULL = the default stream).
+ *
+ * tp_pack / tp_unpack return after the data is complete (they synchronize the stream, as the
+ * paper's timed region does, Sec. 6.3).  The *_async forms only enqueue on the stream; the
+ * caller synchronizes.
+ */
+int tp_pack(const void *inbuf, int incount, tp_type t, void *outbuf, int64_t outsize, int64_t *position,
+            void *hip_stream);
+int tp_unpack(const void *inbuf, int64_t insize, int64_t *position, void *outbuf, int outcount, tp_type t,
+              void *hip_stream);
+int tp_pack_async(const void *inbuf, int incount, tp_type t, void *outbuf, int64_t outsize, int64_t *position,
+                  void *hip_stream);
+int tp_unpack_async(const void *inbuf, int64_t insize, int64_t *position, void *outbuf, int outcount, tp_type t,
+                    void *hip_stream);
+
+/* ---- introspection for tests and ablations ------------------------------------------------------
+ * tp_type_get_strided_block: the canonical form of a committed type (Sec. 3.3): *ndims dimensions,
+ * counts[0] contiguous bytes with strides[0] == 1, dimension d+1 repeats dimension d counts[d+1]
+ * times strides[d+1] bytes apart; *start is the displacement of the first byte from the origin.
+ * Dimensions are in nesting order (the packed stream is row-major over counts, last dimension
+ * slowest), which keeps the MPI type-map order.  An empty type reports ndims 1, counts[0] 0.
+ * counts/strides must have room for TP_MAX_DIMS entries.
+ *
+ * tp_set_override(key, value): force planner choices.  Keys:
+ *   "word"          "0" (automatic) or 1, 2, 4, 8, 16: upper limit on the access width in bytes
+ *   "check_buffers" "1" (default) or "0": skip the per-call memory-residency query
+ * tp_last_plan: describes the kernel launches of the calling thread's most recent
+ * pack/unpack as text (variant, word width, grid), for tests.
+ */
+int tp_type_get_strided_block(tp_type t, int *ndims, int64_t *start, int64_t counts[], int64_t strides[]);
+int tp_set_override(const char *key, const char *value);
+const char *tp_last_plan(void);
+const char *tp_error_string(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TP_PACK_H */

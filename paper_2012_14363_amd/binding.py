@@ -1,0 +1,241 @@
+"""Thin ctypes binding over libtp_pack.so: same names as include/tp_pack.h, argument
+marshalling only.  Every step of the path runs inside the library; without the
+built library (or, for pack/unpack, without a GPU) calls fail loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libtp_pack.so")
+
+TP_TYPE_NULL = -1
+TP_BYTE, TP_CHAR, TP_INT8, TP_UINT8, TP_INT16, TP_UINT16 = 0, 1, 2, 3, 4, 5
+TP_INT32, TP_UINT32, TP_INT64, TP_UINT64, TP_FLOAT, TP_DOUBLE = 6, 7, 8, 9, 10, 11
+TP_ORDER_C, TP_ORDER_FORTRAN = 0, 1
+TP_MAX_DIMS = 16
+
+TP_SUCCESS, TP_ERR_TYPE, TP_ERR_COUNT, TP_ERR_ARG = 0, 1, 2, 3
+TP_ERR_TRUNCATE, TP_ERR_BUFFER, TP_ERR_OTHER, TP_ERR_RANGE = 4, 5, 6, 7
+
+PREDEFINED = {
+    "BYTE": TP_BYTE, "CHAR": TP_CHAR, "INT8": TP_INT8, "UINT8": TP_UINT8, "INT16": TP_INT16,
+    "UINT16": TP_UINT16, "INT32": TP_INT32, "UINT32": TP_UINT32, "INT64": TP_INT64,
+    "UINT64": TP_UINT64, "FLOAT": TP_FLOAT, "DOUBLE": TP_DOUBLE,
+}
+
+# every symbol include/tp_pack.h declares
+EXPORTS = (
+    "tp_type_contiguous", "tp_type_vector", "tp_type_create_hvector", "tp_type_create_subarray",
+    "tp_type_commit", "tp_type_free", "tp_type_size", "tp_type_get_extent", "tp_pack_size",
+    "tp_pack", "tp_unpack", "tp_pack_async", "tp_unpack_async",
+    "tp_type_get_strided_block", "tp_set_override", "tp_last_plan", "tp_error_string",
+)
+
+
+class TpError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: error {code} ({error_string(code)})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library.  Raises if it has not been built (no fallback exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2012_14363_amd.build` "
+                "(there is no CPU or PyTorch fallback for the pack/unpack path)")
+        L = ctypes.CDLL(LIB_PATH)
+        i32, i64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
+        pi32, pi64, pint = ctypes.POINTER(i32), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_int)
+        sig = {
+            "tp_type_contiguous": [ctypes.c_int, i32, pi32],
+            "tp_type_vector": [ctypes.c_int, ctypes.c_int, ctypes.c_int, i32, pi32],
+            "tp_type_create_hvector": [ctypes.c_int, ctypes.c_int, i64, i32, pi32],
+            "tp_type_create_subarray": [ctypes.c_int, pint, pint, pint, ctypes.c_int, i32, pi32],
+            "tp_type_commit": [pi32],
+            "tp_type_free": [pi32],
+            "tp_type_size": [i32, pi64],
+            "tp_type_get_extent": [i32, pi64, pi64],
+            "tp_pack_size": [ctypes.c_int, i32, pi64],
+            "tp_pack": [vp, ctypes.c_int, i32, vp, i64, pi64, vp],
+            "tp_unpack": [vp, i64, pi64, vp, ctypes.c_int, i32, vp],
+            "tp_pack_async": [vp, ctypes.c_int, i32, vp, i64, pi64, vp],
+            "tp_unpack_async": [vp, i64, pi64, vp, ctypes.c_int, i32, vp],
+            "tp_type_get_strided_block": [i32, pint, pi64, pi64, pi64],
+            "tp_set_override": [ctypes.c_char_p, ctypes.c_char_p],
+        }
+        for name, argtypes in sig.items():
+            fn = getattr(L, name)
+            fn.argtypes = argtypes
+            fn.restype = ctypes.c_int
+        L.tp_last_plan.argtypes = []
+        L.tp_last_plan.restype = ctypes.c_char_p
+        L.tp_error_string.argtypes = [ctypes.c_int]
+        L.tp_error_string.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def error_string(code: int) -> str:
+    return lib().tp_error_string(int(code)).decode()
+
+
+def _check(rc: int, where: str):
+    if rc != TP_SUCCESS:
+        raise TpError(rc, where)
+
+
+# ------------------------------------------------------------------ constructors
+def type_contiguous(count: int, old: int) -> int:
+    new = ctypes.c_int32(TP_TYPE_NULL)
+    _check(lib().tp_type_contiguous(count, old, ctypes.byref(new)), "tp_type_contiguous")
+    return new.value
+
+
+def type_vector(count: int, blocklength: int, stride: int, old: int) -> int:
+    new = ctypes.c_int32(TP_TYPE_NULL)
+    _check(lib().tp_type_vector(count, blocklength, stride, old, ctypes.byref(new)), "tp_type_vector")
+    return new.value
+
+
+def type_create_hvector(count: int, blocklength: int, stride_bytes: int, old: int) -> int:
+    new = ctypes.c_int32(TP_TYPE_NULL)
+    _check(lib().tp_type_create_hvector(count, blocklength, stride_bytes, old, ctypes.byref(new)),
+           "tp_type_create_hvector")
+    return new.value
+
+
+def type_create_subarray(sizes, subsizes, starts, order: int, old: int) -> int:
+    n = len(sizes)
+    arr = ctypes.c_int * n
+    new = ctypes.c_int32(TP_TYPE_NULL)
+    _check(lib().tp_type_create_subarray(n, arr(*sizes), arr(*subsizes), arr(*starts), order, old,
+                                         ctypes.byref(new)), "tp_type_create_subarray")
+    return new.value
+
+
+def type_commit(t: int) -> None:
+    h = ctypes.c_int32(t)
+    _check(lib().tp_type_commit(ctypes.byref(h)), "tp_type_commit")
+
+
+def type_free(t: int) -> None:
+    h = ctypes.c_int32(t)
+    _check(lib().tp_type_free(ctypes.byref(h)), "tp_type_free")
+
+
+def type_size(t: int) -> int:
+    v = ctypes.c_int64()
+    _check(lib().tp_type_size(t, ctypes.byref(v)), "tp_type_size")
+    return v.value
+
+
+def type_get_extent(t: int):
+    lb, ex = ctypes.c_int64(), ctypes.c_int64()
+    _check(lib().tp_type_get_extent(t, ctypes.byref(lb), ctypes.byref(ex)), "tp_type_get_extent")
+    return lb.value, ex.value
+
+
+def pack_size(incount: int, t: int) -> int:
+    v = ctypes.c_int64()
+    _check(lib().tp_pack_size(incount, t, ctypes.byref(v)), "tp_pack_size")
+    return v.value
+
+
+def type_get_strided_block(t: int):
+    """(start, counts, strides) of a committed type's canonical StridedBlock."""
+    nd, start = ctypes.c_int(), ctypes.c_int64()
+    counts = (ctypes.c_int64 * TP_MAX_DIMS)()
+    strides = (ctypes.c_int64 * TP_MAX_DIMS)()
+    _check(lib().tp_type_get_strided_block(t, ctypes.byref(nd), ctypes.byref(start), counts, strides),
+           "tp_type_get_strided_block")
+    return start.value, list(counts[:nd.value]), list(strides[:nd.value])
+
+
+def set_override(key: str, value) -> None:
+    _check(lib().tp_set_override(key.encode(), str(value).encode()), "tp_set_override")
+
+
+def last_plan() -> str:
+    return lib().tp_last_plan().decode()
+
+
+# ------------------------------------------------------------------ pack / unpack
+def _ptr(buf) -> int:
+    """Address of a torch tensor (device or pinned host), or a raw integer address."""
+    if isinstance(buf, int):
+        return buf
+    return buf.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def _transfer(fn_name, first, mid, position, stream):
+    pos = ctypes.c_int64(position)
+    fn = getattr(lib(), fn_name)
+    if "unpack" in fn_name:
+        inbuf, insize, outbuf, outcount, t = first, mid[0], mid[1], mid[2], mid[3]
+        rc = fn(_ptr(inbuf), insize, ctypes.byref(pos), _ptr(outbuf), outcount, t, _stream(stream))
+    else:
+        inbuf, incount, t, outbuf, outsize = first, mid[0], mid[1], mid[2], mid[3]
+        rc = fn(_ptr(inbuf), incount, t, _ptr(outbuf), outsize, ctypes.byref(pos), _stream(stream))
+    _check(rc, fn_name)
+    return pos.value
+
+
+def pack(inbuf, incount: int, t: int, outbuf, outsize: int, position: int, stream=None) -> int:
+    """tp_pack; returns the new position."""
+    return _transfer("tp_pack", inbuf, (incount, t, outbuf, outsize), position, stream)
+
+
+def pack_async(inbuf, incount: int, t: int, outbuf, outsize: int, position: int, stream=None) -> int:
+    return _transfer("tp_pack_async", inbuf, (incount, t, outbuf, outsize), position, stream)
+
+
+def unpack(inbuf, insize: int, position: int, outbuf, outcount: int, t: int, stream=None) -> int:
+    """tp_unpack; returns the new position."""
+    return _transfer("tp_unpack", inbuf, (insize, outbuf, outcount, t), position, stream)
+
+
+def unpack_async(inbuf, insize: int, position: int, outbuf, outcount: int, t: int, stream=None) -> int:
+    return _transfer("tp_unpack_async", inbuf, (insize, outbuf, outcount, t), position, stream)
+
+
+# ------------------------------------------------------------------ recipes -> handles
+def type_from_recipe(recipe, commit: bool = True) -> int:
+    """Builds (and by default commits) the datatype a `workloads` recipe names, by
+    calling the constructors; intermediate handles are freed."""
+    kind = recipe[0]
+    if kind == "named":
+        return PREDEFINED[recipe[1]]
+    old = type_from_recipe(recipe[-1], commit=False)
+    if kind == "contiguous":
+        new = type_contiguous(recipe[1], old)
+    elif kind == "vector":
+        new = type_vector(recipe[1], recipe[2], recipe[3], old)
+    elif kind == "hvector":
+        new = type_create_hvector(recipe[1], recipe[2], recipe[3], old)
+    elif kind == "subarray":
+        _, sizes, subs, starts, order, _old = recipe
+        new = type_create_subarray(sizes, subs, starts, TP_ORDER_C if order == "C" else TP_ORDER_FORTRAN, old)
+    else:
+        raise ValueError(kind)
+    if old >= 12:
+        type_free(old)
+    if commit:
+        type_commit(new)
+    return new

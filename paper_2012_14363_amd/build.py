@@ -1,0 +1,44 @@
+"""Builds libtp_pack.so (host C++ + HIP kernels for gfx950) in-tree with hipcc."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(PKG_DIR, "csrc")
+INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
+LIB_PATH = os.path.join(PKG_DIR, "libtp_pack.so")
+
+SOURCES = ["api.cpp", "type_tree.cpp", "canon.cpp", "plan.cpp", "kernels.hip"]
+
+
+def hipcc() -> str:
+    return os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every source for gfx950 and link the shared library.  Always recompiles."""
+    cmd = [
+        hipcc(), "-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
+        # this pool: never let the compiler form packed-fp32 instructions
+        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+        "-Wall", "-Wextra", "-Wno-unused-command-line-argument",
+        "-I", INCLUDE, "-I", CSRC,
+    ]
+    for s in SOURCES:
+        if s.endswith(".cpp"):
+            cmd += ["-x", "hip", os.path.join(CSRC, s)]
+        else:
+            cmd += [os.path.join(CSRC, s)]
+    cmd += ["-o", LIB_PATH]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    subprocess.check_call(cmd)
+    return LIB_PATH
+
+
+if __name__ == "__main__":
+    build(verbose=True)
+    print(LIB_PATH)
+    sys.exit(0)

@@ -1,0 +1,73 @@
+// Pack / unpack kernels for gfx950 (CDNA4, wave64).
+//
+// Pure data movement: the only arithmetic is address computation, so the design
+// goal is to keep as many naturally aligned, coalesced memory accesses in flight
+// as possible.  One kernel template covers every StridedBlock:
+//
+//   * a workgroup of 256 threads is a flat tile of bx lanes along the contiguous
+//     run times 256/bx rows (bx a power of two >= the run length in words, at most
+//     256), so short runs still fill every wavefront with adjacent rows and the
+//     contiguous side of the copy is written (pack) or read (unpack) as one dense
+//     span per wavefront;
+//   * each thread moves UX words along the run and UR rows, issuing all of its
+//     loads before its first store;
+//   * a row index is turned into its byte offset with multiply-shift division by
+//     the (run-time constant) dimension counts; with bx == 256 the row is uniform
+//     across the workgroup and that math runs on the scalar unit;
+//   * all parameters arrive by value in the kernel-argument segment.
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "kernels.hpp"
+#include "tile_body.hpp"
+
+namespace tp {
+
+namespace {
+
+struct DeviceMem {
+    template <class W>
+    __device__ __forceinline__ W load(const char* p) const {
+        return *reinterpret_cast<const W*>(p);
+    }
+    template <class W>
+    __device__ __forceinline__ void store(char* p, const W& v) const {
+        *reinterpret_cast<W*>(p) = v;
+    }
+};
+
+template <int WLOG2, int UX, int UR, bool UNPACK, int NRD>
+__global__ void __launch_bounds__(kBlockThreads) tile_kernel(const KParams p) {
+    tile_thread<WLOG2, UX, UR, UNPACK, NRD>(p, blockIdx.x, threadIdx.x, DeviceMem{});
+}
+
+using KernelFn = void (*)(const KParams);
+
+template <bool UNPACK>
+struct PickKernel {
+    KernelFn fn = nullptr;
+    template <int WLOG2, int UX, int UR, int NRD>
+    void operator()() {
+        fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD>;
+    }
+};
+
+}  // namespace
+
+hipError_t enqueue(const Launch& l, bool unpack, hipStream_t stream) {
+    const KParams p = kernel_params(l);
+    KernelFn fn = nullptr;
+    if (unpack) {
+        PickKernel<true> pick;
+        if (dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, pick)) fn = pick.fn;
+    } else {
+        PickKernel<false> pick;
+        if (dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, pick)) fn = pick.fn;
+    }
+    if (!fn || l.nblocks == 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(fn, dim3(l.nblocks), dim3(kBlockThreads), 0, stream, p);
+    return hipGetLastError();
+}
+
+}  // namespace tp

@@ -1,0 +1,13 @@
+// Device side: the pack/unpack kernels and their launcher.
+#pragma once
+
+#include <hip/hip_runtime_api.h>
+
+#include "plan.hpp"
+
+namespace tp {
+
+// Enqueues one planned launch on `stream`.  Returns hipSuccess or the launch error.
+hipError_t enqueue(const Launch& launch, bool unpack, hipStream_t stream);
+
+}  // namespace tp

@@ -1,0 +1,164 @@
+#include "plan.hpp"
+
+#include <algorithm>
+#include <cstdio>
+
+#include "status.hpp"
+
+namespace tp {
+
+namespace {
+
+struct Dim {
+    int64_t count;
+    int64_t stride;
+};
+
+int ceil_log2(uint64_t v) {
+    int s = 0;
+    while ((uint64_t{1} << s) < v) ++s;
+    return s;
+}
+
+// Thread-tile shape for runs of n0 words (Sec. 3.3 maps X to the run and fills the
+// block with further rows; here the block is flat and the split is a power of two).
+void choose_tile(uint32_t n0, Launch* l) {
+    if (n0 >= 4u * kBlockThreads) {
+        l->p.bx_log2 = 8;
+        l->ux = 4;
+        l->ur = 1;
+    } else if (n0 > static_cast<uint32_t>(kBlockThreads)) {
+        l->p.bx_log2 = 8;
+        l->ux = n0 <= 2u * kBlockThreads ? 2 : 4;
+        l->ur = 4 / l->ux;
+    } else {
+        l->p.bx_log2 = static_cast<uint32_t>(ceil_log2(n0));
+        l->ux = 1;
+        l->ur = 4;
+    }
+}
+
+struct Splitter {
+    const PlanInput& in;
+    int word_log2;
+    int64_t row_pitch;  // bytes of a full run in the packed stream
+    std::vector<Launch>* out;
+
+    // One launch over dims[0..nd): dims[0].count bytes per run (a multiple of the word).
+    void add(const std::vector<Dim>& dims, const char* typed, char* packed) {
+        Launch l;
+        l.word_log2 = word_log2;
+        KParams& p = l.p;
+        p.strided = typed;
+        p.packed = packed;
+        p.row_pitch = row_pitch;
+        p.n0 = static_cast<uint32_t>(dims[0].count >> word_log2);
+        uint64_t rows = 1;
+        p.nrd = 0;
+        for (size_t d = 1; d < dims.size(); ++d) {
+            if (dims[d].count == 1) continue;
+            p.rcount[p.nrd] = static_cast<uint32_t>(dims[d].count);
+            p.rstride[p.nrd] = dims[d].stride;
+            p.rdiv[p.nrd] = make_fastdiv(p.rcount[p.nrd]);
+            ++p.nrd;
+            rows *= static_cast<uint64_t>(dims[d].count);
+        }
+        p.nrows = static_cast<uint32_t>(rows);
+        choose_tile(p.n0, &l);
+        const uint32_t bx = 1u << p.bx_log2;
+        const uint32_t br = kBlockThreads >> p.bx_log2;
+        p.nxc = (p.n0 + bx * l.ux - 1) / (bx * l.ux);
+        p.xc_div = make_fastdiv(p.nxc);
+        const uint64_t nrc = (rows + uint64_t{br} * l.ur - 1) / (uint64_t{br} * l.ur);
+        l.nblocks = static_cast<uint32_t>(nrc * p.nxc);
+        out->push_back(l);
+    }
+
+    // Largest row count for which block ids stay below 2^30 with runs of n0 words.
+    int64_t row_limit(int64_t n0) const {
+        Launch probe;
+        choose_tile(static_cast<uint32_t>(n0), &probe);
+        const int64_t bx = int64_t{1} << probe.p.bx_log2;
+        const int64_t br = kBlockThreads >> probe.p.bx_log2;
+        const int64_t nxc = (n0 + bx * probe.ux - 1) / (bx * probe.ux);
+        const int64_t by_blocks = ((int64_t{1} << 30) / nxc) * br * probe.ur;
+        return std::max<int64_t>(1, std::min(in.max_rows_per_launch, by_blocks));
+    }
+
+    // Rows: split the outermost dimension until a launch's row count fits.
+    void split_rows(std::vector<Dim> dims, const char* typed, char* packed) {
+        int64_t rows = 1;
+        for (size_t d = 1; d < dims.size(); ++d) rows *= dims[d].count;
+        const int64_t limit = row_limit(dims[0].count >> word_log2);
+        if (rows <= limit) {
+            add(dims, typed, packed);
+            return;
+        }
+        const Dim top = dims.back();
+        const int64_t inner_rows = rows / top.count;
+        const int64_t chunk = std::max<int64_t>(1, limit / inner_rows);
+        for (int64_t i = 0; i < top.count; i += chunk) {
+            const int64_t k = std::min(chunk, top.count - i);
+            std::vector<Dim> sub = dims;
+            if (inner_rows > limit) sub.pop_back(); else sub.back().count = k;
+            split_rows(sub, typed + i * top.stride, packed + i * inner_rows * row_pitch);
+        }
+    }
+
+    // Runs longer than the per-launch word limit are cut into pieces along dimension 0.
+    void split_runs(const std::vector<Dim>& dims, const char* typed, char* packed) {
+        const int64_t piece = in.max_words_per_run << word_log2;
+        for (int64_t off = 0; off < dims[0].count; off += piece) {
+            std::vector<Dim> sub = dims;
+            sub[0].count = std::min(piece, dims[0].count - off);
+            split_rows(sub, typed + off, packed + off);
+        }
+    }
+};
+
+}  // namespace
+
+int plan_launches(const PlanInput& in, std::vector<Launch>* out) {
+    out->clear();
+    const StridedBlock& sb = in.block;
+    if (in.count == 0 || sb.counts[0] == 0) return kSuccess;
+
+    std::vector<Dim> dims;
+    for (int d = 0; d < sb.ndims; ++d) dims.push_back({sb.counts[d], sb.strides[d]});
+    // The object count is one more outer dimension of stride `extent` (Sec. 3.3 handles it
+    // with the grid's Z dimension); fold or flatten it away when objects abut.
+    if (in.count > 1) {
+        Dim& top = dims.back();
+        const int64_t top_span = dims.size() == 1 ? top.count : top.count * top.stride;
+        if (in.extent == top_span) top.count *= in.count;
+        else dims.push_back({in.count, in.extent});
+    }
+    if (dims.size() - 1 > static_cast<size_t>(kMaxDims)) return kErrRange;
+
+    // Word width: the widest power of two (at most 16 bytes) that divides the run length,
+    // every stride and both start addresses, so that each access is naturally aligned.
+    const char* typed = in.typed + sb.start;
+    uint64_t bits = static_cast<uint64_t>(dims[0].count) | reinterpret_cast<uintptr_t>(typed) |
+                    reinterpret_cast<uintptr_t>(in.packed);
+    for (size_t d = 1; d < dims.size(); ++d)
+        bits |= static_cast<uint64_t>(dims[d].stride < 0 ? -dims[d].stride : dims[d].stride);
+    int word_log2 = std::min(4, in.max_word_log2);
+    if (bits != 0) word_log2 = std::min(word_log2, __builtin_ctzll(bits));
+
+    Splitter s{in, word_log2, dims[0].count, out};
+    s.split_runs(dims, typed, in.packed);
+    return kSuccess;
+}
+
+std::string describe(const std::vector<Launch>& launches) {
+    std::string text;
+    char line[256];
+    for (const Launch& l : launches) {
+        std::snprintf(line, sizeof line, "tile W=%d ux=%d ur=%d bx=%u n0=%u rows=%u nrd=%u blocks=%u\n",
+                      1 << l.word_log2, l.ux, l.ur, 1u << l.p.bx_log2, l.p.n0, l.p.nrows, l.p.nrd, l.nblocks);
+        text += line;
+    }
+    return text;
+}
+
+}  // namespace tp

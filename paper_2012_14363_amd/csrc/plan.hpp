@@ -1,0 +1,63 @@
+// Call-time planning (paper Sec. 3.3, "Kernel Selection"): from a committed type's
+// StridedBlock plus what is only known at the call - object count, buffer
+// addresses - to a list of kernel launches with all parameters by value.
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "fastdiv.hpp"
+#include "strided_block.hpp"
+
+namespace tp {
+
+constexpr int kBlockThreads = 256;  // four wave64 per workgroup
+
+// Everything one kernel launch needs; passed by value in the kernel-argument
+// segment, so no datatype metadata ever lives in device memory.
+//
+// The launch covers `nrows` runs of `n0` words of W bytes.  Row r is element
+// (i_0, i_1, ...) of the row dimensions (r = i_0 + rcount[0]*(i_1 + ...)); its
+// bytes sit at strided + sum(i_d * rstride[d]) and at packed + r * row_pitch.
+struct KParams {
+    const char* strided = nullptr;  // typed buffer: origin + start (+ split offset)
+    char* packed = nullptr;         // contiguous buffer + position (+ split offset)
+    int64_t row_pitch = 0;          // bytes between consecutive rows in the packed stream
+    uint32_t n0 = 0;                // words per run
+    uint32_t nrows = 0;
+    uint32_t bx_log2 = 0;           // lanes along a run = 1 << bx_log2; the other lanes take further rows
+    uint32_t nxc = 1;               // x-chunks per row; block id = row_chunk * nxc + x_chunk
+    uint32_t nrd = 0;               // row dimensions in use
+    FastDiv xc_div;
+    FastDiv rdiv[kMaxDims];
+    uint32_t rcount[kMaxDims] = {};
+    int64_t rstride[kMaxDims] = {};
+};
+
+struct Launch {
+    KParams p;
+    int word_log2 = 0;  // W = 1 << word_log2 bytes per lane access
+    int ux = 1;         // words per thread along the run
+    int ur = 1;         // rows per thread
+    uint32_t nblocks = 0;
+};
+
+struct PlanInput {
+    StridedBlock block;
+    int64_t extent = 0;      // distance between consecutive objects
+    int64_t count = 0;       // objects
+    const char* typed = nullptr;   // origin of object 0 in the typed buffer
+    char* packed = nullptr;        // contiguous buffer + position
+    int max_word_log2 = 4;   // override: cap on the access width
+    int64_t max_rows_per_launch = int64_t{1} << 30;   // tests lower these to force splitting
+    int64_t max_words_per_run = int64_t{1} << 30;
+};
+
+// Fills `out` (cleared first).  Returns a TP_* status.
+int plan_launches(const PlanInput& in, std::vector<Launch>* out);
+
+// One line per launch, for tp_last_plan().
+std::string describe(const std::vector<Launch>& launches);
+
+}  // namespace tp

@@ -1,0 +1,127 @@
+// Host emulation of the planned kernel launches, for tests only.
+//
+// Compiles the library's planner (plan.cpp) and the very same per-thread kernel
+// body (tile_body.hpp) with the host compiler and runs every workgroup and thread
+// of every launch sequentially, with each memory access checked: inside the
+// buffer it belongs to, naturally aligned, and (optionally) no destination byte
+// written twice.  It exists so that index and bounds mistakes show up on the CPU
+// instead of as a GPU memory fault.  Nothing in the product path uses it.
+#include <cstdint>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "plan.hpp"
+#include "status.hpp"
+#include "tile_body.hpp"
+
+namespace {
+
+struct Checks {
+    const char* typed_lo;
+    const char* typed_hi;
+    const char* packed_lo;
+    const char* packed_hi;
+    uint8_t* write_count;  // one counter per destination byte, or null
+    const char* dst_lo;
+    int64_t oob = 0, misaligned = 0, rewritten = 0;
+};
+
+struct HostMem {
+    Checks* c;
+    bool inside(const char* p, size_t n) const {
+        return (p >= c->typed_lo && p + n <= c->typed_hi) || (p >= c->packed_lo && p + n <= c->packed_hi);
+    }
+    template <class W>
+    W load(const char* p) const {
+        W v{};
+        if (!inside(p, sizeof(W))) { c->oob++; return v; }
+        if (reinterpret_cast<uintptr_t>(p) % sizeof(W)) c->misaligned++;
+        std::memcpy(&v, p, sizeof(W));
+        return v;
+    }
+    template <class W>
+    void store(char* p, const W& v) const {
+        if (!inside(p, sizeof(W))) { c->oob++; return; }
+        if (reinterpret_cast<uintptr_t>(p) % sizeof(W)) c->misaligned++;
+        if (c->write_count)
+            for (size_t i = 0; i < sizeof(W); ++i)
+                if (c->write_count[p - c->dst_lo + static_cast<long>(i)]++) c->rewritten++;
+        std::memcpy(p, &v, sizeof(W));
+    }
+};
+
+template <bool UNPACK>
+struct RunLaunch {
+    const tp::KParams* p;
+    uint32_t nblocks;
+    HostMem mem;
+    template <int WLOG2, int UX, int UR, int NRD>
+    void operator()() {
+        for (uint32_t b = 0; b < nblocks; ++b)
+            for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t)
+                tp::tile_thread<WLOG2, UX, UR, UNPACK, NRD>(*p, b, t, mem);
+    }
+};
+
+}  // namespace
+
+extern "C" {
+
+// Runs pack (unpack == 0) or unpack of `count` objects described by the StridedBlock
+// (ndims, start, counts, strides) and `extent`, between host buffers:
+//   typed  buffer [typed_buf, typed_buf + typed_len), objects' origin at typed_buf + origin
+//   packed buffer [packed_buf, packed_buf + packed_len), data at packed_buf + position
+// write_count (may be null) has one byte per byte of the destination buffer.
+// result[0..2] = accesses out of bounds, misaligned, destination bytes written twice;
+// result[3] = number of launches.  `plan_text` receives the plan description.
+// Returns a TP_* status from the planner, or 100 if a launch names no kernel variant.
+int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, const int64_t* strides, int64_t extent,
+                  int64_t count, char* typed_buf, int64_t typed_len, int64_t origin, char* packed_buf,
+                  int64_t packed_len, int64_t position, int max_word_log2, int64_t max_rows_per_launch,
+                  int64_t max_words_per_run, uint8_t* write_count, int64_t* result, char* plan_text,
+                  int64_t plan_text_len) {
+    tp::PlanInput in;
+    in.block.ndims = ndims;
+    in.block.start = start;
+    for (int d = 0; d < ndims; ++d) {
+        in.block.counts[d] = counts[d];
+        in.block.strides[d] = strides[d];
+    }
+    in.extent = extent;
+    in.count = count;
+    in.typed = typed_buf + origin;
+    in.packed = packed_buf + position;
+    in.max_word_log2 = max_word_log2;
+    in.max_rows_per_launch = max_rows_per_launch;
+    in.max_words_per_run = max_words_per_run;
+    std::vector<tp::Launch> launches;
+    const int rc = tp::plan_launches(in, &launches);
+    if (rc != tp::kSuccess) return rc;
+    if (plan_text && plan_text_len > 0) {
+        const std::string text = tp::describe(launches);
+        std::snprintf(plan_text, static_cast<size_t>(plan_text_len), "%s", text.c_str());
+    }
+    Checks c{typed_buf, typed_buf + typed_len, packed_buf, packed_buf + packed_len, write_count,
+             unpack ? typed_buf : packed_buf};
+    for (const tp::Launch& l : launches) {
+        const tp::KParams p = tp::kernel_params(l);
+        bool found;
+        if (unpack) {
+            RunLaunch<true> run{&p, l.nblocks, HostMem{&c}};
+            found = tp::dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, run);
+        } else {
+            RunLaunch<false> run{&p, l.nblocks, HostMem{&c}};
+            found = tp::dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, run);
+        }
+        if (!found) return 100;
+    }
+    result[0] = c.oob;
+    result[1] = c.misaligned;
+    result[2] = c.rewritten;
+    result[3] = static_cast<int64_t>(launches.size());
+    return 0;
+}
+
+}  // extern "C"

@@ -1,0 +1,371 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle,
+byte for byte, on the same seeded inputs.  Needs a real MI355X (-m gpu)."""
+import os
+import random
+import sys
+
+import numpy as np
+import pytest
+
+import workloads as W
+from workloads import BYTE, DOUBLE, FLOAT, contiguous, hvector, named, subarray, vector
+from oracle import typemap as py
+from oracle import typemap_c as cc
+from paper_2012_14363_amd import binding as tp
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def say(*a):
+    print(*a, flush=True)
+    sys.stdout.flush()
+
+
+@pytest.fixture(scope="module")
+def dev():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    tp.lib()  # fails loudly if the HIP library is not built
+    return torch.device("cuda:0")
+
+
+def to_dev(a: np.ndarray, dev):
+    return torch.from_numpy(a).to(dev)
+
+
+def roundtrip(t, incount, dev, *, typed_shift=0, packed_shift=0, position=0, seed=0, check_unpack=True,
+              pinned_packed=False):
+    """pack on the GPU == oracle pack; unpack on the GPU into a poisoned buffer == oracle unpack."""
+    h = tp.type_from_recipe(t)
+    size = tp.type_size(h) * incount
+    ex = tp.type_get_extent(h)[1]
+    d, n = cc.blocks(t, incount)
+    lo = min(0, int(d.min())) if d.size else 0
+    hi = max(0, int((d + n).max())) if d.size else 0
+    pad = 64
+    origin = -lo + pad + typed_shift
+    nbytes = hi - lo + 2 * pad + typed_shift
+    typed_h = W.random_bytes(seed, nbytes)
+    typed_d = to_dev(typed_h, dev)
+    if pinned_packed:
+        store = torch.full((position + size + 64,), 0xEE, dtype=torch.uint8).pin_memory()
+    else:
+        store = torch.full((position + size + 64,), 0xEE, dtype=torch.uint8, device=dev)
+    packed_d = store[packed_shift:packed_shift + position + size]
+    new_pos = tp.pack(typed_d.data_ptr() + origin, incount, h, packed_d, position + size, position)
+    assert new_pos == position + size
+    expect = np.full(position + size, 0xEE, dtype=np.uint8)
+    cc.pack(typed_h, origin, incount, t, expect, position)
+    got = store.cpu().numpy()
+    assert np.array_equal(got[packed_shift:packed_shift + position + size], expect), (t, tp.last_plan())
+    assert (got[:packed_shift] == 0xEE).all() and (got[packed_shift + position + size:] == 0xEE).all()
+
+    if check_unpack and not pinned_packed:
+        dst_d = torch.full((nbytes,), 0xA5, dtype=torch.uint8, device=dev)
+        new_pos = tp.unpack(packed_d, position + size, position, dst_d.data_ptr() + origin, incount, h)
+        assert new_pos == position + size
+        want = np.full(nbytes, 0xA5, dtype=np.uint8)
+        cc.unpack(expect, position, want, origin, incount, t)
+        assert np.array_equal(dst_d.cpu().numpy(), want), (t, tp.last_plan())
+    if h >= 12:
+        tp.type_free(h)
+
+
+# ------------------------------------------------------------------ small and ragged
+def test_random_small_types(dev):
+    rng = random.Random(401)
+    done = 0
+    while done < 120:
+        t = W.random_recipe(rng, rng.randint(1, 4), allow_negative=True)
+        if py.size(t) > 4096:
+            continue
+        incount = rng.randint(1, 3)
+        overlap = py.has_overlap(t, incount)
+        say("random type", done, t, "incount", incount)
+        roundtrip(t, incount, dev, typed_shift=rng.choice((0, 1, 2, 4, 8)), packed_shift=rng.choice((0, 1, 2, 4, 8)),
+                  position=rng.choice((0, 3, 16)), seed=done, check_unpack=not overlap)
+        done += 1
+
+
+@pytest.mark.parametrize("a0", [1, 2, 3, 4, 8, 16, 24, 48, 64, 200, 512, 1040, 4048, 4100, 4112, 20000])
+def test_tile_shapes_and_ragged_tails(dev, a0):
+    say("tile shapes a0", a0)
+    # several tiles in every direction plus a ragged tail, 3D with incount and 2D
+    roundtrip(hvector(5, 1, 37 * 20480, hvector(37, 1, 20480, contiguous(a0, BYTE))), 2, dev, seed=a0)
+    roundtrip(vector(1031, a0, a0 + 16, BYTE), 1, dev, seed=a0 + 1)
+
+
+def test_word_widths_forced(dev):
+    t = vector(300, 64, 96, BYTE)
+    try:
+        for w in (1, 2, 4, 8, 16):
+            say("forced word", w)
+            tp.set_override("word", w)
+            roundtrip(t, 2, dev, seed=w)
+            assert f"W={w} " in tp.last_plan()
+    finally:
+        tp.set_override("word", 0)
+
+
+def test_launch_splitting_on_gpu(dev):
+    t = hvector(7, 1, 4096, hvector(5, 1, 512, vector(9, 16, 32, BYTE)))
+    try:
+        tp.set_override("max_rows_per_launch", 11)
+        tp.set_override("max_words_per_run", 3)
+        say("split launches")
+        roundtrip(t, 3, dev, seed=5)
+        assert tp.last_plan().count("\n") > 10
+    finally:
+        tp.set_override("max_rows_per_launch", 1 << 30)
+        tp.set_override("max_words_per_run", 1 << 30)
+
+
+def test_empty_and_degenerate(dev):
+    say("empty / degenerate")
+    buf = torch.zeros(64, dtype=torch.uint8, device=dev)
+    out = torch.full((64,), 7, dtype=torch.uint8, device=dev)
+    empty = tp.type_from_recipe(vector(0, 2, 4, BYTE))
+    assert tp.pack(buf, 5, empty, out, 64, 9) == 9
+    one = tp.type_from_recipe(contiguous(1, BYTE))
+    assert tp.pack(buf, 0, one, out, 64, 9) == 9
+    assert tp.pack(buf, 1, one, out, 10, 9) == 10           # exactly fits
+    with pytest.raises(tp.TpError) as e:
+        tp.pack(buf, 2, one, out, 10, 9)
+    assert e.value.code == tp.TP_ERR_TRUNCATE
+    assert (out.cpu().numpy()[10:] == 7).all()
+    roundtrip(BYTE, 1, dev)
+    roundtrip(DOUBLE, 7, dev, typed_shift=8)
+    roundtrip(contiguous(1 << 20, BYTE), 1, dev, typed_shift=1, packed_shift=3)   # unaligned plain copy
+
+
+def test_pageable_host_memory_is_rejected(dev):
+    host = np.zeros(64, dtype=np.uint8)
+    out = torch.zeros(64, dtype=torch.uint8, device=dev)
+    t = tp.type_from_recipe(vector(3, 2, 4, BYTE))
+    with pytest.raises(tp.TpError) as e:
+        tp.pack(host.ctypes.data, 1, t, out, 64, 0)
+    assert e.value.code == tp.TP_ERR_BUFFER
+    pinned = torch.zeros(64, dtype=torch.uint8).pin_memory()
+    with pytest.raises(tp.TpError) as e:   # the typed side must be device memory
+        tp.pack(pinned, 1, t, out, 64, 0)
+    assert e.value.code == tp.TP_ERR_BUFFER
+    # the library still works afterwards
+    roundtrip(vector(3, 2, 4, BYTE), 1, dev)
+
+
+# ------------------------------------------------------------------ the five workloads
+def test_cfg1_both_constructions(dev):
+    c = W.configs.cfg1()
+    src_h = W.random_bytes(c["seed"], c["buffer_bytes"])
+    src = to_dev(src_h, dev)
+    outs = []
+    for name, r in c["recipes"].items():
+        say("cfg1", name)
+        h = tp.type_from_recipe(r)
+        assert tp.type_get_strided_block(h) == (0, [8, 64], [1, 512])
+        out = torch.zeros(512, dtype=torch.uint8, device=dev)
+        assert tp.pack(src, 1, h, out, 512, 0) == 512
+        expect = np.zeros(512, np.uint8)
+        cc.pack(src_h, 0, 1, r, expect, 0)
+        assert np.array_equal(out.cpu().numpy(), expect)
+        assert np.array_equal(expect, src_h[:64 * 512].reshape(64, 512)[:, :8].reshape(-1))
+        back = torch.full((c["buffer_bytes"],), 0xA5, dtype=torch.uint8, device=dev)
+        assert tp.unpack(out, 512, 0, back, 1, h) == 512
+        want = np.full(c["buffer_bytes"], 0xA5, np.uint8)
+        cc.unpack(expect, 0, want, 0, 1, r)
+        assert np.array_equal(back.cpu().numpy(), want)
+        outs.append(expect)
+    assert np.array_equal(outs[0], outs[1])
+
+
+@pytest.mark.parametrize("a0", W.configs.A0_SWEEP)
+def test_cfg2_1mib_full(dev, a0):
+    p = W.configs.cfg2_point(a0, 1 << 20)
+    say("cfg2 1MiB a0", a0, p["a"], "alloc", p["alloc_bytes"] >> 20, "MiB")
+    src = W.fills.counter_bytes_torch(p["seed"], p["alloc_bytes"], dev)
+    src_h = src.cpu().numpy()
+    h = tp.type_from_recipe(p["recipe"])
+    out = torch.zeros(1 << 20, dtype=torch.uint8, device=dev)
+    assert tp.pack(src, 1, h, out, 1 << 20, 0) == 1 << 20
+    expect = np.zeros(1 << 20, np.uint8)
+    cc.pack(src_h, 0, 1, p["recipe"], expect, 0, nthreads=8)
+    assert np.array_equal(out.cpu().numpy(), expect), tp.last_plan()
+    a0_, a1, a2 = p["a"]
+    assert np.array_equal(expect, src_h.reshape(-1, 512, 512)[:a2, :a1, :a0].reshape(-1))
+    back = torch.full((p["alloc_bytes"],), 0xA5, dtype=torch.uint8, device=dev)
+    assert tp.unpack(out, 1 << 20, 0, back, 1, h) == 1 << 20
+    want = np.full(p["alloc_bytes"], 0xA5, np.uint8)
+    cc.unpack(expect, 0, want, 0, 1, p["recipe"], nthreads=8)
+    assert torch.equal(back.cpu(), torch.from_numpy(want)), tp.last_plan()
+
+
+@pytest.mark.parametrize("a0", W.configs.A0_SWEEP)
+def test_cfg2_64mib_sampled(dev, a0):
+    # full benchmark size; the allocation reaches 32 GiB, so outputs are checked on samples the
+    # oracle computes one by one (packed byte k against the source byte its type map names)
+    p = W.configs.cfg2_point(a0, 1 << 26)
+    say("cfg2 64MiB a0", a0, p["a"], "alloc", p["alloc_bytes"] >> 20, "MiB")
+    src = W.fills.counter_bytes_torch(p["seed"], p["alloc_bytes"], dev)
+    h = tp.type_from_recipe(p["recipe"])
+    n = 1 << 26
+    out = torch.zeros(n, dtype=torch.uint8, device=dev)
+    assert tp.pack(src, 1, h, out, n, 0) == n
+    got = out.cpu().numpy()
+    a0_, a1, a2 = p["a"]
+    rng = np.random.default_rng(a0)
+    ks = np.unique(np.concatenate([rng.integers(0, n, 200000), np.arange(0, 4096), np.arange(n - 4096, n)]))
+    # source displacement of packed byte k by the subarray definition (x fastest, then y, then z)
+    x, y, z = ks % a0_, (ks // a0_) % a1, ks // (a0_ * a1)
+    disp = x + 512 * y + 512 * 512 * z
+    assert np.array_equal(got[ks], W.fills.counter_byte_at(p["seed"], disp)), tp.last_plan()
+    # and the oracle's own type map on a prefix of whole rows
+    d, ln = cc.blocks(hvector(min(a2, 2), 1, 512 * 512, hvector(a1, 1, 512, contiguous(a0_, BYTE))))
+    first = np.repeat(d, ln) + (np.arange(int(ln.sum())) - np.repeat(np.cumsum(ln) - ln, ln))
+    assert np.array_equal(got[:first.size], W.fills.counter_byte_at(p["seed"], first))
+    # unpack into a poisoned allocation, then compare selected samples and the bytes around them
+    del src
+    back = torch.full((p["alloc_bytes"],), 0xA5, dtype=torch.uint8, device=dev)
+    assert tp.unpack(out, n, 0, back, 1, h) == n
+    idx = torch.from_numpy(disp).to(dev)
+    assert np.array_equal(back[idx].cpu().numpy(), got[ks])
+    # checksum: the whole allocation holds the packed bytes plus poison, nothing else
+    total = int(back.sum(dtype=torch.int64).item())
+    assert total == int(got.sum(dtype=np.int64)) + 0xA5 * (p["alloc_bytes"] - n)
+    if a0_ < 512:
+        gap = torch.from_numpy(disp[x == a0_ - 1] + 1).to(dev)   # first byte after a run's end
+        assert (back[gap] == 0xA5).all()
+
+
+def test_cfg3_halo_full(dev):
+    c = W.configs.cfg3()
+    say("cfg3 generating grid")
+    grid_h = W.random_grid_f64(c["seed"], c["grid_shape"])
+    raw_h = grid_h.reshape(-1).view(np.uint8)
+    grid = to_dev(raw_h, dev)
+    send = [tp.type_from_recipe(r) for r in c["send"]]
+    ghost = [tp.type_from_recipe(r) for r in c["ghost_for_send"]]
+    total = sum(tp.type_size(h) for h in send)
+    assert total == 37308096
+    packed = torch.zeros(total, dtype=torch.uint8, device=dev)
+    pos = 0
+    expect = np.zeros(total, np.uint8)
+    epos = 0
+    for i, (h, r) in enumerate(zip(send, c["send"])):
+        say("cfg3 pack", i, c["directions"][i])
+        pos = tp.pack(grid, 1, h, packed, total, pos)
+        epos = cc.pack(raw_h, 0, 1, r, expect, epos)
+        assert pos == epos
+    assert pos == total
+    assert np.array_equal(packed.cpu().numpy(), expect)
+    # numpy slices as a third opinion on the first and last regions
+    for i in (0, 12, 25):
+        reg = c["send_region"][i]
+        sel = np.ascontiguousarray(grid_h[tuple(slice(a, b) for a, b in reg)]).reshape(-1).view(np.uint8)
+        off = sum(tp.type_size(h) for h in send[:i])
+        assert np.array_equal(expect[off:off + sel.size], sel)
+    # unpack every message into the ghost zone of the opposite direction
+    pos = 0
+    epos = 0
+    want = raw_h.copy()
+    for i, (h, r) in enumerate(zip(ghost, c["ghost_for_send"])):
+        say("cfg3 unpack", i)
+        pos = tp.unpack(packed, total, pos, grid, 1, h)
+        epos = cc.unpack(expect, epos, want, 0, 1, r)
+    assert pos == epos == total
+    got = grid.cpu().numpy()
+    assert np.array_equal(got, want)
+    g = got.view(np.float64).reshape(c["grid_shape"])
+    for i in (0, 13, 25):   # periodic self-exchange: ghost(-d) now equals the interior send(d)
+        s_reg, g_reg = c["send_region"][i], c["ghost_region_for_send"][i]
+        assert np.array_equal(g[tuple(slice(a, b) for a, b in g_reg)], grid_h[tuple(slice(a, b) for a, b in s_reg)])
+
+
+@pytest.mark.parametrize("bl", W.configs.CFG4_BLOCKLENGTHS)
+def test_cfg4_tiny_runs_full(dev, bl):
+    p = W.configs.cfg4_point(bl)
+    src = W.fills.counter_bytes_torch(p["seed"], p["source_bytes"], dev)
+    src_h = src.cpu().numpy()
+    n = p["packed_bytes"]
+    h = tp.type_from_recipe(p["recipe"])
+    for k in W.configs.CFG4_OFFSETS:
+        for position in ((0, 1) if k in (0, 5) else (0,)):
+            say("cfg4 bl", bl, "offset", k, "position", position)
+            out = torch.zeros(n + position, dtype=torch.uint8, device=dev)
+            assert tp.pack(src.data_ptr() + k, 1, h, out, n + position, position) == n + position
+            expect = np.ascontiguousarray(src_h[k:k + (1 << 24) * 64].reshape(-1, 64)[:, :bl]).reshape(-1)
+            got = out.cpu().numpy()
+            assert np.array_equal(got[position:], expect), tp.last_plan()
+            if k in (0, 3):
+                ref = np.zeros(n, np.uint8)
+                cc.pack(src_h, k, 1, p["recipe"], ref, 0, nthreads=8)
+                assert np.array_equal(ref, expect)
+            if k in (0, 5):
+                back = torch.full((p["source_bytes"],), 0xA5, dtype=torch.uint8, device=dev)
+                assert tp.unpack(out, n + position, position, back.data_ptr() + k, 1, h) == n + position
+                b = back.cpu().numpy()
+                rows = b[k:k + (1 << 24) * 64].reshape(-1, 64)
+                assert np.array_equal(rows[:, :bl].reshape(-1), expect)
+                assert (rows[:, bl:] == 0xA5).all() and (b[:k] == 0xA5).all() and (b[k + (1 << 30):] == 0xA5).all()
+    # the same layout with the offset inside the type (subarray start)
+    hs = tp.type_from_recipe(p["recipe_subarray"](5))
+    out = torch.zeros(n, dtype=torch.uint8, device=dev)
+    tp.pack(src, 1, hs, out, n, 0)
+    assert np.array_equal(out.cpu().numpy(), np.ascontiguousarray(src_h[5:5 + (1 << 30)].reshape(-1, 64)[:, :bl]).reshape(-1))
+
+
+def test_cfg5_nested_batch(dev):
+    c = W.configs.cfg5()
+    r = c["recipe"]
+    h = tp.type_from_recipe(r)
+    ex = tp.type_get_extent(h)[1]
+    size = tp.type_size(h)
+    nobj = c["objects"]
+    say("cfg5 generating", nobj * ex >> 20, "MiB")
+    src = W.fills.counter_bytes_torch(c["seed"], nobj * ex, dev)
+    out = torch.zeros(nobj * size, dtype=torch.uint8, device=dev)
+    say("cfg5 one call, incount", nobj)
+    assert tp.pack(src, nobj, h, out, nobj * size, 0) == nobj * size
+    src_h = src.cpu().numpy()
+    expect = np.zeros(nobj * size, np.uint8)
+    say("cfg5 oracle")
+    cc.pack(src_h, 0, nobj, r, expect, 0, nthreads=16)
+    assert np.array_equal(out.cpu().numpy(), expect), tp.last_plan()
+    # 1000 enqueue-only calls and one synchronize
+    say("cfg5 async calls")
+    out.zero_()
+    pos = 0
+    for i in range(nobj):
+        pos = tp.pack_async(src.data_ptr() + i * ex, 1, h, out, nobj * size, pos)
+    torch.cuda.synchronize()
+    assert pos == nobj * size
+    assert np.array_equal(out.cpu().numpy(), expect)
+    # zero-copy: the packed stream written straight into pinned host memory
+    say("cfg5 pinned host")
+    few = 64
+    pinned = torch.zeros(few * size, dtype=torch.uint8).pin_memory()
+    assert tp.pack(src, few, h, pinned, few * size, 0) == few * size
+    assert np.array_equal(pinned.numpy(), expect[:few * size])
+
+
+def test_pinned_host_packed_side(dev):
+    say("pinned packed side, small types")
+    roundtrip(vector(1031, 24, 40, BYTE), 2, dev, pinned_packed=True, seed=3)
+    roundtrip(hvector(37, 1, 20480, contiguous(4100, BYTE)), 1, dev, pinned_packed=True, packed_shift=4, seed=4)
+    # unpack from pinned host memory as well
+    t = vector(513, 16, 48, BYTE)
+    h = tp.type_from_recipe(t)
+    size = tp.type_size(h)
+    ex = tp.type_get_extent(h)[1]
+    packed_h = W.random_bytes(9, size)
+    pinned = torch.from_numpy(packed_h).pin_memory()
+    dst = torch.full((ex,), 0xA5, dtype=torch.uint8, device=dev)
+    assert tp.unpack(pinned, size, 0, dst, 1, h) == size
+    want = np.full(ex, 0xA5, np.uint8)
+    cc.unpack(packed_h, 0, want, 0, 1, t)
+    assert np.array_equal(dst.cpu().numpy(), want)
+
+
+def test_counter_fill_matches_on_device(dev):
+    a = W.fills.counter_bytes_torch(77, 100003, dev, chunk_words=4099).cpu().numpy()
+    assert np.array_equal(a, W.fills.counter_bytes_numpy(77, 0, 100003))

@@ -1,0 +1,322 @@
+"""CPU-only tests of the library's host logic: type sizes/bounds, canonicalization
+(paper Sec. 3.1-3.3) against the oracle's type map, the C ABI's error behaviour and
+exported symbols, and the planner + kernel body emulated on the host under bounds
+checks.  No GPU compute call is made here."""
+import ctypes
+import os
+import random
+import re
+import sys
+
+import numpy as np
+import pytest
+
+import workloads as W
+from workloads import BYTE, DOUBLE, FLOAT, contiguous, hvector, named, subarray, vector
+from oracle import typemap as py
+from oracle import typemap_c as cc
+from paper_2012_14363_amd import binding as tp
+
+sys.path.insert(0, os.path.dirname(os.path.abspath(__file__)))
+import host_emul  # noqa: E402
+
+INT16 = named("INT16")
+
+
+def expand(block, count=1, extent=0):
+    """Byte displacements a StridedBlock selects, row-major over counts (last dim slowest)."""
+    start, counts, strides = block
+    out = []
+
+    def rec(d, base):
+        if d == 0:
+            out.extend(range(base, base + counts[0]))
+            return
+        for i in range(counts[d]):
+            rec(d - 1, base + i * strides[d])
+
+    for obj in range(count):
+        rec(len(counts) - 1, start + obj * extent)
+    return out
+
+
+# ------------------------------------------------------------------ ABI surface
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(os.path.dirname(tp.LIB_PATH), "..", "include", "tp_pack.h")).read()
+    declared = set(re.findall(r"\b(tp_[a-z_0-9]+)\s*\(", header))
+    assert declared == set(tp.EXPORTS)
+    lib = tp.lib()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_predefined_types():
+    for name, h in tp.PREDEFINED.items():
+        assert tp.type_size(h) == py.NAMED_SIZE[name]
+        assert tp.type_get_extent(h) == (0, py.NAMED_SIZE[name])
+        assert tp.type_get_strided_block(h) == (0, [py.NAMED_SIZE[name]], [1])
+
+
+# ------------------------------------------------------------------ canonical forms
+def test_config_canonical_forms():
+    b = lambda r: tp.type_get_strided_block(tp.type_from_recipe(r))  # noqa: E731
+    # 2D vector: both constructions give the same block
+    for r in W.configs.cfg1()["recipes"].values():
+        assert b(r) == (0, [8, 64], [1, 512])
+    # 3D strided block: generic, flattened (a1 = 512), dense-folded (a0 = 512), fully dense
+    assert b(W.configs.cfg2_point(16, 1 << 20)["recipe"]) == (0, [16, 256, 256], [1, 512, 262144])
+    assert b(W.configs.cfg2_point(4, 1 << 20)["recipe"]) == (0, [4, 1 << 18], [1, 512])
+    assert b(W.configs.cfg2_point(512, 1 << 20)["recipe"]) == (0, [32768, 32], [1, 262144])
+    assert b(W.configs.cfg2_point(512, 1 << 26)["recipe"]) == (0, [1 << 26], [1])
+    # halo: the 8-byte element folds into the x run; nothing else merges
+    c3 = W.configs.cfg3()
+    shapes = set()
+    for r, reg in zip(c3["send"], c3["send_region"]):
+        start, counts, strides = b(r)
+        (z0, z1), (y0, y1), (x0, x1) = reg
+        assert start == ((z0 * 512 + y0) * 512 + x0) * 8
+        assert counts == [8 * (x1 - x0), y1 - y0, z1 - z0] and strides == [1, 4096, 2097152]
+        shapes.add(tuple(counts))
+    assert shapes == {(24, 506, 506), (4048, 3, 506), (4048, 506, 3), (4048, 3, 3), (24, 506, 3), (24, 3, 506),
+                      (24, 3, 3)}
+    # tiny runs
+    assert b(W.configs.cfg4_point(3)["recipe"]) == (0, [3, 1 << 24], [1, 64])
+    assert b(W.configs.cfg4_point(3)["recipe_subarray"](5)) == (5, [3, 1 << 24], [1, 64])
+    # 4-level nested type: 4D, strides not monotone because nesting order is kept
+    t5 = tp.type_from_recipe(W.configs.cfg5()["recipe"])
+    assert tp.type_get_strided_block(t5) == (50432, [4096, 8, 16, 4], [1, 16384, 8192, 2342912])
+    assert tp.type_size(t5) == 2097152 and tp.type_get_extent(t5) == (0, 8200192)
+
+
+def test_each_pass_on_its_own():
+    b = lambda r: tp.type_get_strided_block(tp.type_from_recipe(r))  # noqa: E731
+    # dense folding (Alg. 2): a stream of abutting dense elements is one dense run
+    assert b(contiguous(10, FLOAT)) == (0, [40], [1])
+    assert b(vector(5, 4, 4, BYTE)) == (0, [20], [1])
+    # ... but not when the oldtype has holes: contiguous(3, {0,2}) stays strided
+    assert b(contiguous(3, vector(2, 1, 2, BYTE))) == (0, [1, 2, 3], [1, 2, 3])
+    # stream elision (Alg. 3): count-1 streams vanish, their offsets survive
+    assert b(hvector(1, 1, 9999, vector(4, 2, 8, BYTE))) == b(vector(4, 2, 8, BYTE)) == (0, [2, 4], [1, 8])
+    assert b(subarray((7, 9), (1, 3), (2, 4), "C", BYTE)) == (2 * 9 + 4, [3], [1])
+    # stream flattening (Alg. 4): rows whose pitch continues the inner stream
+    assert b(hvector(6, 1, 40, hvector(5, 1, 8, INT16))) == (0, [2, 30], [1, 8])
+    # the paper's worked sizes (Sec. 3.1 figure caption): 100 x 13 x 47 bytes in 256 x 512 x 1024
+    assert b(subarray((1024, 512, 256), (47, 13, 100), (0, 0, 0), "C", BYTE)) == (0, [100, 13, 47], [1, 256, 131072])
+    assert b(hvector(47, 1, 256 * 512, vector(13, 100, 256, BYTE))) == (0, [100, 13, 47], [1, 256, 131072])
+    # ... and with FLOAT elements and the row pitch counted in elements
+    assert b(subarray((1024, 512, 256), (47, 13, 100), (0, 0, 0), "C", FLOAT)) == (0, [400, 13, 47],
+                                                                                    [1, 1024, 524288])
+    # Fortran order reverses which dimension is contiguous
+    assert b(subarray((256, 512, 1024), (100, 13, 47), (0, 0, 0), "F", BYTE)) == (0, [100, 13, 47], [1, 256, 131072])
+    # nesting order is kept: same byte set, other order, other block
+    assert b(hvector(3, 1, 8, hvector(2, 1, 2, BYTE))) == (0, [1, 2, 3], [1, 2, 8])
+    assert b(hvector(2, 1, 2, hvector(3, 1, 8, BYTE))) == (0, [1, 3, 2], [1, 8, 2])
+    # empty types
+    assert b(vector(0, 2, 4, BYTE)) == (0, [0], [1])
+    assert b(subarray((4, 6), (2, 0), (1, 2), "C", BYTE)) == (0, [0], [1])
+
+
+def _equivalent_cuboids(e, a):
+    from test_oracle_pins import _cuboids
+    return _cuboids(e, a)
+
+
+def test_paper_equivalent_constructions_share_one_block():
+    blocks = {str(tp.type_get_strided_block(tp.type_from_recipe(t))) for t in _equivalent_cuboids((5, 3, 4), (8, 6, 5))}
+    assert blocks == {str((0, [20, 3, 4], [1, 32, 192]))}
+
+
+def _random_types(seed, n, **kw):
+    rng = random.Random(seed)
+    out = []
+    while len(out) < n:
+        t = W.random_recipe(rng, rng.randint(1, 4), **kw)
+        if py.size(t) <= 2048:
+            out.append(t)
+    return out
+
+
+def test_canonical_block_expands_to_the_oracle_type_map():
+    # what pins the canonicalizer: for thousands of random trees (negative strides, zero counts,
+    # self-overlap included) the StridedBlock enumerates exactly the oracle's byte sequence
+    seen = {}
+    for t in _random_types(201, 3000, allow_negative=True, allow_zero=True, allow_overlap=True):
+        h = tp.type_from_recipe(t)
+        block = tp.type_get_strided_block(h)
+        disp = py.byte_displacements(t)
+        assert expand(block) == disp, t
+        assert tp.type_size(h) == py.size(t), t
+        lb, ub = py.bounds(t)
+        assert tp.type_get_extent(h) == (lb, ub - lb), t
+        key = tuple(disp)
+        if not py.has_overlap(t) and disp:
+            # identical ordered type maps must give the identical block
+            assert seen.setdefault(key, block) == block, t
+        if h >= 12:
+            tp.type_free(h)
+    assert len(seen) > 300
+
+
+def test_incount_objects_follow_extent():
+    for t in _random_types(202, 200, allow_negative=True):
+        h = tp.type_from_recipe(t)
+        ex = tp.type_get_extent(h)[1]
+        assert expand(tp.type_get_strided_block(h), 3, ex) == py.byte_displacements(t, 3)
+        assert tp.pack_size(3, h) == 3 * py.size(t)
+
+
+# ------------------------------------------------------------------ error behaviour
+def test_error_codes_and_unchanged_outputs():
+    L = tp.lib()
+    new = ctypes.c_int32(777)
+    assert L.tp_type_contiguous(-1, tp.TP_BYTE, ctypes.byref(new)) == tp.TP_ERR_COUNT
+    assert L.tp_type_vector(2, -3, 1, tp.TP_BYTE, ctypes.byref(new)) == tp.TP_ERR_COUNT
+    assert L.tp_type_contiguous(2, 12345678, ctypes.byref(new)) == tp.TP_ERR_TYPE
+    assert L.tp_type_contiguous(2, -5, ctypes.byref(new)) == tp.TP_ERR_TYPE
+    assert L.tp_type_contiguous(2, tp.TP_BYTE, None) == tp.TP_ERR_ARG
+    arr = ctypes.c_int * 2
+    sub = L.tp_type_create_subarray
+    assert sub(2, arr(4, 6), arr(5, 1), arr(0, 0), 0, tp.TP_BYTE, ctypes.byref(new)) == tp.TP_ERR_ARG
+    assert sub(2, arr(4, 6), arr(2, 3), arr(3, 0), 0, tp.TP_BYTE, ctypes.byref(new)) == tp.TP_ERR_ARG
+    assert sub(2, arr(4, 6), arr(2, 3), arr(0, 0), 7, tp.TP_BYTE, ctypes.byref(new)) == tp.TP_ERR_ARG
+    assert sub(0, arr(4, 6), arr(2, 3), arr(0, 0), 0, tp.TP_BYTE, ctypes.byref(new)) == tp.TP_ERR_ARG
+    assert sub(2, arr(4, 6), arr(2, -3), arr(0, 0), 0, tp.TP_BYTE, ctypes.byref(new)) == tp.TP_ERR_ARG
+    big = ctypes.c_int32()
+    assert L.tp_type_vector(2 ** 31 - 1, 2 ** 31 - 1, 2 ** 31 - 1, tp.TP_BYTE, ctypes.byref(big)) == tp.TP_SUCCESS
+    assert L.tp_type_vector(2 ** 31 - 1, 2 ** 31 - 1, 1, big, ctypes.byref(new)) == tp.TP_ERR_RANGE
+    assert new.value == 777
+
+    t = tp.type_vector(3, 2, 4, tp.TP_BYTE)
+    pos = ctypes.c_int64(5)
+    fake = ctypes.c_void_p(4096)
+    # not committed yet
+    assert L.tp_pack(fake, 1, t, fake, 100, ctypes.byref(pos), None) == tp.TP_ERR_TYPE
+    nd, st = ctypes.c_int(), ctypes.c_int64()
+    c16 = (ctypes.c_int64 * 16)()
+    assert L.tp_type_get_strided_block(t, ctypes.byref(nd), ctypes.byref(st), c16, c16) == tp.TP_ERR_TYPE
+    tp.type_commit(t)
+    tp.type_commit(t)  # idempotent
+    assert L.tp_pack(fake, -1, t, fake, 100, ctypes.byref(pos), None) == tp.TP_ERR_COUNT
+    assert L.tp_pack(fake, 1, t, fake, 10, ctypes.byref(pos), None) == tp.TP_ERR_TRUNCATE   # 5 + 6 > 10
+    assert L.tp_unpack(fake, 10, ctypes.byref(pos), fake, 1, t, None) == tp.TP_ERR_TRUNCATE
+    assert L.tp_pack(None, 1, t, fake, 100, ctypes.byref(pos), None) == tp.TP_ERR_BUFFER
+    assert L.tp_pack(fake, 1, t, None, 100, ctypes.byref(pos), None) == tp.TP_ERR_BUFFER
+    assert L.tp_pack(fake, 1, t, fake, 100, None, None) == tp.TP_ERR_ARG
+    neg = ctypes.c_int64(-1)
+    assert L.tp_pack(fake, 1, t, fake, 100, ctypes.byref(neg), None) == tp.TP_ERR_ARG
+    assert pos.value == 5 and neg.value == -1
+    # zero objects: a successful no-op that needs no buffers and no device
+    assert L.tp_pack(None, 0, t, None, 0, ctypes.byref(ctypes.c_int64(0)), None) == tp.TP_SUCCESS
+    empty = tp.type_from_recipe(vector(0, 2, 4, BYTE))
+    assert L.tp_pack(None, 5, empty, None, 0, ctypes.byref(ctypes.c_int64(0)), None) == tp.TP_SUCCESS
+
+    h = ctypes.c_int32(t)
+    assert L.tp_type_free(ctypes.byref(h)) == tp.TP_SUCCESS and h.value == tp.TP_TYPE_NULL
+    assert L.tp_type_size(t, ctypes.byref(ctypes.c_int64())) == tp.TP_ERR_TYPE        # stale handle
+    assert L.tp_type_free(ctypes.byref(ctypes.c_int32(tp.TP_BYTE))) == tp.TP_ERR_TYPE  # predefined
+    assert L.tp_set_override(b"no_such_key", b"1") == tp.TP_ERR_ARG
+    assert L.tp_set_override(b"word", b"3") == tp.TP_ERR_ARG
+    for code in range(0, 9):
+        assert tp.error_string(code)
+
+
+def test_freeing_the_oldtype_keeps_the_derived_type_alive():
+    row = tp.type_contiguous(8, tp.TP_BYTE)
+    plane = tp.type_create_hvector(64, 1, 512, row)
+    tp.type_free(row)
+    tp.type_commit(plane)
+    assert tp.type_get_strided_block(plane) == (0, [8, 64], [1, 512])
+    # a recycled slot must not resurrect the stale handle
+    other = tp.type_contiguous(3, tp.TP_BYTE)
+    with pytest.raises(tp.TpError):
+        tp.type_size(row)
+    tp.type_free(other)
+    tp.type_free(plane)
+
+
+# ------------------------------------------- planner + kernel body, emulated on the host
+def _emulate_roundtrip(t, incount, *, typed_shift=0, packed_shift=0, position=0, **kw):
+    h = tp.type_from_recipe(t)
+    block = tp.type_get_strided_block(h)
+    lb, ex = tp.type_get_extent(h)
+    size = tp.type_size(h) * incount
+    # a subarray's bounds are those of the full array even when its oldtype reaches below its
+    # origin, so size the buffer from the bytes actually selected
+    disps = py.byte_displacements(t, incount)
+    lo, hi = min(0, min(disps)), max(0, max(disps) + 1)
+    pad = 32
+    origin = -lo + pad + typed_shift
+    n = hi - lo + 2 * pad + typed_shift
+    rng = np.random.default_rng(hash((str(t), incount)) & 0xFFFFFFFF)
+    typed_store = np.zeros(n + 64, dtype=np.uint8)
+    base = (-typed_store.ctypes.data) % 64          # 64-byte aligned window, then shifted
+    typed = typed_store[base:base + n]
+    typed[:] = rng.integers(0, 256, n, dtype=np.uint8)
+    packed_store = np.zeros(size + position + 64 + 16, dtype=np.uint8)
+    pbase = (-packed_store.ctypes.data) % 64 + packed_shift
+    packed = packed_store[pbase:pbase + position + size]
+    packed[:] = 0xEE
+
+    res = host_emul.transfer(False, block, ex, incount, typed, origin, packed, position, **kw)
+    assert res["rc"] == 0 and res["oob"] == 0 and res["misaligned"] == 0 and res["rewritten"] == 0, (t, res)
+    expect = np.full(position + size, 0xEE, dtype=np.uint8)
+    assert cc.pack(typed, origin, incount, t, expect, position) == position + size
+    assert np.array_equal(packed, expect), (t, res["plan"])
+    assert (res["write_count"][position:] == 1).all() and (res["write_count"][:position] == 0).all()
+
+    if not py.has_overlap(t, incount):
+        dst = np.full(n, 0xA5, dtype=np.uint8)
+        res = host_emul.transfer(True, block, ex, incount, dst, origin, packed, position, **kw)
+        assert res["rc"] == 0 and res["oob"] == 0 and res["misaligned"] == 0 and res["rewritten"] == 0, (t, res)
+        want = np.full(n, 0xA5, dtype=np.uint8)
+        cc.unpack(packed, position, want, origin, incount, t)
+        assert np.array_equal(dst, want), (t, res["plan"])
+    if h >= 12:
+        tp.type_free(h)
+    return res
+
+
+def test_emulated_kernels_match_oracle_on_random_types():
+    rng = random.Random(303)
+    for i, t in enumerate(_random_types(301, 250, allow_negative=True, allow_zero=False)):
+        _emulate_roundtrip(t, rng.randint(1, 3), typed_shift=rng.choice((0, 0, 1, 2, 4, 8)),
+                           packed_shift=rng.choice((0, 0, 1, 2, 4, 8)), position=rng.choice((0, 3, 16)))
+
+
+@pytest.mark.parametrize("a0", [1, 2, 4, 8, 16, 48, 64, 200, 512, 1040, 4100, 4112])
+def test_emulated_tile_shapes(a0):
+    # run lengths that exercise every (ux, ur) tile and ragged tails, 2D and 3D
+    _emulate_roundtrip(hvector(3, 1, 5 * 8192, hvector(5, 1, 8192, contiguous(a0, BYTE))), 2)
+    _emulate_roundtrip(vector(37, a0, a0 + 16, BYTE), 1)
+
+
+def test_emulated_word_width_follows_alignment():
+    t = vector(16, 32, 64, BYTE)
+    for shift, word in ((0, 16), (8, 8), (4, 4), (2, 2), (1, 1)):
+        assert f"W={word} " in _emulate_roundtrip(t, 1, typed_shift=shift)["plan"]
+        assert f"W={word} " in _emulate_roundtrip(t, 1, packed_shift=shift)["plan"]
+        assert f"W={word} " in _emulate_roundtrip(t, 1, position=shift)["plan"]
+    assert "W=4 " in _emulate_roundtrip(t, 1, max_word=4)["plan"]
+    assert "W=8 " in _emulate_roundtrip(vector(16, 24, 64, BYTE), 1)["plan"]
+    assert "W=1 " in _emulate_roundtrip(vector(16, 3, 64, BYTE), 1)["plan"]
+    assert "W=2 " in _emulate_roundtrip(vector(16, 4, 6, BYTE), 1)["plan"]       # stride 6
+    assert "W=4 " in _emulate_roundtrip(vector(2, 16, 17, FLOAT), 3)["plan"]     # extent 132
+
+
+def test_emulated_launch_splitting():
+    t = hvector(7, 1, 4096, hvector(5, 1, 512, vector(9, 16, 32, BYTE)))
+    one = _emulate_roundtrip(t, 3)
+    assert one["launches"] == 1
+    assert _emulate_roundtrip(t, 3, max_rows_per_launch=100)["launches"] > 1
+    assert _emulate_roundtrip(t, 3, max_rows_per_launch=7)["launches"] > 10
+    assert _emulate_roundtrip(t, 3, max_rows_per_launch=1)["launches"] == 3 * 7 * 5 * 9
+    assert _emulate_roundtrip(t, 2, max_words_per_run=1, max_word=4)["launches"] == 4
+    long_rows = vector(3, 5000, 6000, BYTE)
+    assert _emulate_roundtrip(long_rows, 2, max_words_per_run=100, max_rows_per_launch=4)["launches"] > 4
+
+
+def test_emulated_objects_that_abut_are_merged():
+    # extent == size: incount objects are one longer run / one longer stream
+    assert "rows=1 " in _emulate_roundtrip(contiguous(64, BYTE), 5)["plan"]
+    sub = subarray((8, 64), (8, 16), (0, 0), "C", BYTE)   # extent 512 = 8 rows of pitch 64
+    assert "rows=40 nrd=1" in _emulate_roundtrip(sub, 5)["plan"]
