@@ -51,6 +51,13 @@ def lib() -> ctypes.CDLL:
             raise RuntimeError(
                 f"{LIB_PATH} is missing: build it with `python -m paper_2012_14363_amd.build` "
                 "(there is no CPU or PyTorch fallback for the pack/unpack path)")
+        # One HIP runtime per process: PyTorch ships its own libamdhip64.  Import it first so the
+        # loader resolves this library's dependency to that already-loaded runtime; loaded the
+        # other way round the process would hold two runtimes that cannot see each other's memory.
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         L = ctypes.CDLL(LIB_PATH)
         i32, i64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
         pi32, pi64, pint = ctypes.POINTER(i32), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_int)
