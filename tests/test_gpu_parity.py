@@ -30,6 +30,11 @@ def dev():
     return torch.device("cuda:0")
 
 
+def dev_sum(t, chunk=1 << 28) -> int:
+    """Sum of a uint8 device tensor, in chunks (an int64 upcast of tens of GiB would not fit)."""
+    return sum(int(t[i:i + chunk].sum(dtype=torch.int64).item()) for i in range(0, t.numel(), chunk))
+
+
 def to_dev(a: np.ndarray, dev):
     return torch.from_numpy(a).to(dev)
 
@@ -230,7 +235,7 @@ def test_cfg2_64mib_sampled(dev, a0):
     idx = torch.from_numpy(disp).to(dev)
     assert np.array_equal(back[idx].cpu().numpy(), got[ks])
     # checksum: the whole allocation holds the packed bytes plus poison, nothing else
-    total = int(back.sum(dtype=torch.int64).item())
+    total = dev_sum(back)
     assert total == int(got.sum(dtype=np.int64)) + 0xA5 * (p["alloc_bytes"] - n)
     if a0_ < 512:
         gap = torch.from_numpy(disp[x == a0_ - 1] + 1).to(dev)   # first byte after a run's end
