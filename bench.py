@@ -1,0 +1,308 @@
+#!/usr/bin/env python3
+"""Benchmark of the pack/unpack hot path on one MI355X.
+
+Workload (config.workload): the 3D strided-block sweep - a0 x a1 x a2 byte
+sub-blocks of a 512 x 512 x e2 byte allocation, a0 in {1,...,512}, 64 MiB packed
+per point.  One step = for every one of the 10 points: build and commit the
+datatype (translate, canonicalize, StridedBlock, plan), pack it, and - after all
+packs - unpack every point back into its typed buffer; the a0 = 512 point is the
+fully dense 1D path.  Calls are enqueued with the *_async entry points and the
+step ends with one stream synchronize.  Inputs are resident in HBM before the
+timed region.  value = bytes read + bytes written by the method (2 x packed
+bytes per pack or unpack) / wall time.
+
+Prints ONE JSON line.  `roofline` is for the kernel that takes most of the step;
+`kernels` lists every point.  `cpu_baseline` is the CPU oracle on a bounded
+sample of the same sweep.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+PACKED_BYTES = 1 << 26
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--packed-bytes", type=int, default=PACKED_BYTES, help="packed bytes per sweep point")
+    ap.add_argument("--override", action="append", default=[], metavar="KEY=VALUE",
+                    help="planner override passed to tp_set_override (ablations), e.g. nt=0 or word=4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the secondary measurements")
+    return ap.parse_args()
+
+
+def sector_bound_fraction(run: int, granule: int = 128) -> float:
+    """Reachable fraction of peak for the algorithmic metric when every run of `run` bytes on the
+    strided side costs whole `granule`-byte memory transactions: 2r / (g*ceil(r/g) + r).
+    Measured on MI355X (FETCH_SIZE): a strided read brings in whole 128-byte lines."""
+    g = granule
+    return 2.0 * run / (g * ((run + g - 1) // g) + run)
+
+
+# HBM bytes per launch of the sweep's kernels at 64 MiB packed, from rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE runs of this script (profiles/cfg2_sweep_64MiB_hbm_traffic.md): counter KiB x 1024 x the
+# factor a plain 64 MiB copy calibrates (FETCH_SIZE reads half the known bytes: x2; WRITE_SIZE: x1).
+# Keyed by (op, a0): (bytes fetched, bytes written).
+MEASURED_TRAFFIC = {
+    ('pack', 1): (8586295699, 68514624),
+    ('pack', 2): (4293162371, 67108864),
+    ('pack', 4): (2146595196, 67108864),
+    ('pack', 8): (1073312567, 67108864),
+    ('pack', 16): (536670805, 67108864),
+    ('pack', 32): (268348581, 67108864),
+    ('pack', 64): (134187021, 67108864),
+    ('pack', 128): (67107329, 67108864),
+    ('pack', 256): (67106817, 67108864),
+    ('pack', 512): (67108864, 67108864),
+    ('unpack', 1): (90740879, 2147483648),
+    ('unpack', 2): (67112191, 1073741824),
+    ('unpack', 4): (67111679, 536870912),
+    ('unpack', 8): (67113342, 268435456),
+    ('unpack', 16): (67113086, 134217728),
+    ('unpack', 32): (67110271, 67108864),
+    ('unpack', 64): (67110016, 67108864),
+    ('unpack', 128): (67110143, 67108864),
+    ('unpack', 256): (67109888, 67108864),
+    ('unpack', 512): (67108864, 67108864),
+}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported "
+              "(no collectives or sharding in this path).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import workloads as W
+    from paper_2012_14363_amd import binding as tp
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    tp.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    stream = torch.cuda.current_stream()
+
+    # ---------------------------------------------------------------- inputs, resident in HBM
+    points = W.configs.cfg2_sweep(args.packed_bytes)
+    align = 1 << 21
+    bases, total = [], 0
+    for p in points:
+        bases.append(total)
+        total += (p["alloc_bytes"] + align - 1) // align * align
+    arena = W.fills.counter_bytes_torch(W.configs.SEED_BASE + 1, total, dev)
+    packed = [torch.zeros(p["packed_bytes"], dtype=torch.uint8, device=dev) for p in points]
+    torch.cuda.synchronize()
+    for kv in args.override:
+        key, _, val = kv.partition("=")
+        tp.set_override(key, val)
+
+    def run_step(events=None):
+        handles = []
+        for i, p in enumerate(points):
+            h = tp.type_from_recipe(p["recipe"])          # construct + commit
+            handles.append(h)
+            if events is not None:
+                events[0][i][0].record(stream)
+            tp.pack_async(arena.data_ptr() + bases[i], 1, h, packed[i], p["packed_bytes"], 0, stream)
+            if events is not None:
+                events[0][i][1].record(stream)
+        for i, p in enumerate(points):
+            if events is not None:
+                events[1][i][0].record(stream)
+            tp.unpack_async(packed[i], p["packed_bytes"], 0, arena.data_ptr() + bases[i], 1, handles[i], stream)
+            if events is not None:
+                events[1][i][1].record(stream)
+        stream.synchronize()                               # completion
+        for h in handles:
+            if h >= 12:
+                tp.type_free(h)
+
+    for _ in range(args.warmup):
+        run_step()
+    plans = []
+    for i, p in enumerate(points):
+        h = tp.type_from_recipe(p["recipe"])
+        tp.pack(arena.data_ptr() + bases[i], 1, h, packed[i], p["packed_bytes"], 0, stream)
+        plans.append(tp.last_plan().strip())
+
+    def new_events():
+        return [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in points]
+                for _ in range(2)]
+
+    all_events = [new_events() for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        run_step(all_events[k])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    step_s = (t1 - t0) / args.steps
+    bytes_per_step = sum(2 * p["packed_bytes"] for p in points) * 2   # pack + unpack, read + write
+    value = bytes_per_step / step_s / 1e9
+
+    # per-call device times from the HIP events recorded inside the timed region
+    kernels = []
+    for d, op in enumerate(("pack", "unpack")):
+        for i, p in enumerate(points):
+            ms = [all_events[k][d][i][0].elapsed_time(all_events[k][d][i][1]) for k in range(args.steps)]
+            avg_us = 1e3 * sum(ms) / len(ms)
+            alg = 2 * p["packed_bytes"]
+            run = int(plans[i].split("n0=")[1].split()[0]) * int(plans[i].split("W=")[1].split()[0])
+            kernels.append({
+                "op": op, "a": list(p["a"]), "plan": plans[i], "avg_us": round(avg_us, 2),
+                "algorithmic_bytes": alg, "gbs": round(alg / avg_us / 1e3, 1),
+                "frac_of_peak": round(alg / avg_us / 1e3 / HBM_PEAK_GBS, 4),
+                "sector_bound_frac_g128": round(sector_bound_fraction(run), 4),
+            })
+    dominant = max(kernels, key=lambda k: k["avg_us"])
+    roofline = {
+        "bound": "hbm", "kernel": f"{dominant['op']} a={dominant['a']} [{dominant['plan']}]",
+        "achieved": dominant["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": round(dominant["gbs"] / HBM_PEAK_GBS, 4),
+        "avg_launch_us": dominant["avg_us"], "algorithmic_bytes_per_launch": dominant["algorithmic_bytes"],
+        "traffic": None,
+        "sector_bound_frac_g128": dominant["sector_bound_frac_g128"],
+    }
+    measured = MEASURED_TRAFFIC.get((dominant["op"], dominant["a"][0]))
+    if measured and args.packed_bytes == PACKED_BYTES and not args.override:
+        roofline["traffic"] = sum(measured)
+        roofline["traffic_fetch_write"] = list(measured)
+
+    out = {
+        "metric": "pack/unpack GB/s (read+write)", "value": round(value, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(step_s * 1e3, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "3D strided-block sweep, a0 in {1..512}, 64 MiB packed per point, "
+                               "512x512xE2 byte allocation, pack+unpack of all 10 points per step",
+                   "packed_bytes_per_point": args.packed_bytes, "points": len(points),
+                   "overrides": args.override, "bytes_per_step": bytes_per_step, "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4)},
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(W, np)
+    if not args.no_extras:
+        out["extras"] = extras(W, tp, torch, np, dev, stream)
+    print(json.dumps(out))
+
+
+def cpu_baseline(W, np):
+    """The CPU oracle (C twin) on a bounded sample of the same sweep: 8 MiB packed per point
+    (the outermost dimension cut to 1/8), pack + unpack of all 10 points, all host cores."""
+    from oracle import typemap_c as cc
+
+    cores = len(os.sched_getaffinity(0))
+    sample_bytes = 1 << 23
+    pts = W.configs.cfg2_sweep(sample_bytes)
+    biggest = max(p["alloc_bytes"] for p in pts)
+    src = np.empty(biggest, dtype=np.uint8)
+    src.view(np.uint64)[:] = np.arange(biggest // 8, dtype=np.uint64) * np.uint64(0x9E3779B97F4A7C15)
+    outs = [np.zeros(p["packed_bytes"], np.uint8) for p in pts]
+    for p, o in zip(pts[-2:], outs[-2:]):  # warm the code path
+        cc.pack(src, 0, 1, p["recipe"], o, 0, nthreads=cores)
+    t0 = time.perf_counter()
+    reps = 0
+    while True:
+        for p, o in zip(pts, outs):
+            cc.pack(src, 0, 1, p["recipe"], o, 0, nthreads=cores)
+        for p, o in zip(pts, outs):
+            cc.unpack(o, 0, src, 0, 1, p["recipe"], nthreads=cores)
+        reps += 1
+        if time.perf_counter() - t0 > 10.0 or reps >= 20:
+            break
+    dt = time.perf_counter() - t0
+    moved = reps * sum(2 * p["packed_bytes"] for p in pts) * 2
+    return {"value": round(moved / dt / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "sample": f"same sweep at 8 MiB packed per point (outermost dimension / 8), {reps} passes of "
+                      f"pack+unpack over all 10 points, {cores} threads over the outermost loop"}
+
+
+def extras(W, tp, torch, np, dev, stream):
+    """Secondary measurements: copy ceiling, synchronous-call latency, commit time per type."""
+    res = {}
+
+    def timed(fn, n=20, warm=3):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for a, b in ev:
+            a.record(stream)
+            fn()
+            b.record(stream)
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in ev)
+        return ts[len(ts) // 2] * 1e3  # median, us
+
+    # copy ceiling: torch's device-to-device copy of 64 MiB, rotating over 1.5 GiB so caches do not help
+    n = 1 << 26
+    srcs = [torch.empty(n, dtype=torch.uint8, device=dev).fill_(i) for i in range(12)]
+    dsts = [torch.empty(n, dtype=torch.uint8, device=dev) for _ in range(12)]
+    k = [0]
+
+    def copy():
+        dsts[k[0] % 12].copy_(srcs[k[0] % 12])
+        k[0] += 1
+    us = timed(copy, n=24)
+    res["copy_ceiling_torch_64MiB"] = {"us": round(us, 2), "gbs": round(2 * n / us / 1e3, 1)}
+
+    byte_t = tp.type_from_recipe(W.contiguous(n, W.BYTE))
+
+    def own_copy():
+        tp.pack_async(srcs[k[0] % 12], 1, byte_t, dsts[k[0] % 12], n, 0, stream)
+        k[0] += 1
+    us = timed(own_copy, n=24)
+    res["copy_ceiling_tp_1d_64MiB"] = {"us": round(us, 2), "gbs": round(2 * n / us / 1e3, 1)}
+    del srcs, dsts
+
+    # synchronous-call latency (launch + kernel + synchronize, the paper's timed region) on the small 2D vector
+    c1 = W.configs.cfg1()
+    buf = torch.zeros(c1["buffer_bytes"], dtype=torch.uint8, device=dev)
+    out = torch.zeros(512, dtype=torch.uint8, device=dev)
+    h = tp.type_from_recipe(c1["recipes"]["vector"])
+    lat = []
+    for _ in range(200):
+        t0 = time.perf_counter()
+        tp.pack(buf, 1, h, out, 512, 0, stream)
+        lat.append(time.perf_counter() - t0)
+    lat.sort()
+    res["sync_pack_latency_us_2d_vector_512B"] = round(lat[len(lat) // 2] * 1e6, 2)
+
+    # commit time per type: trimean over construct+commit+free cycles (paper Sec. 6.1 statistic)
+    rows = []
+    for family, recipe in W.configs.commit_recipes():
+        ts = []
+        for _ in range(3000):
+            t0 = time.perf_counter()
+            hh = tp.type_from_recipe(recipe)
+            t1 = time.perf_counter()
+            tp.type_free(hh)
+            ts.append(t1 - t0)
+        ts.sort()
+        q1, q2, q3 = ts[len(ts) // 4], ts[len(ts) // 2], ts[3 * len(ts) // 4]
+        rows.append({"family": family, "construct_commit_trimean_us": round((q1 + 2 * q2 + q3) / 4 * 1e6, 2)})
+    res["canonicalize_us_per_type_via_python_binding"] = rows
+    return res
+
+
+if __name__ == "__main__":
+    main()

@@ -145,6 +145,10 @@ int tp_unpack_async(const void *inbuf, int64_t insize, int64_t *position, void *
  * tp_set_override(key, value): force planner choices.  Keys:
  *   "word"          "0" (automatic) or 1, 2, 4, 8, 16: upper limit on the access width in bytes
  *   "check_buffers" "1" (default) or "0": skip the per-call memory-residency query
+ *   "nt"            "-1" (automatic) or 0..3: streaming hints, bit 0 = non-temporal loads,
+ *                   bit 1 = non-temporal stores
+ *   "max_rows_per_launch", "max_words_per_run"  1 .. 2^30: split limits (tests lower them to
+ *                   exercise the multi-launch path on small inputs)
  * tp_last_plan: describes the kernel launches of the calling thread's most recent
  * pack/unpack as text (variant, word width, grid), for tests.
  */

@@ -22,6 +22,7 @@ namespace {
 using namespace tp;
 
 std::atomic<int> g_max_word_log2{4};
+std::atomic<int> g_nt{-1};
 std::atomic<bool> g_check_buffers{true};
 std::atomic<int64_t> g_max_rows_per_launch{int64_t{1} << 30};
 std::atomic<int64_t> g_max_words_per_run{int64_t{1} << 30};
@@ -122,6 +123,8 @@ int transfer(bool unpack, const void* typed_buf, int64_t count, tp_type t, const
     in.typed = typed_view;
     in.packed = const_cast<char*>(packed_view) + *position;
     in.max_word_log2 = g_max_word_log2.load(std::memory_order_relaxed);
+    in.nt = g_nt.load(std::memory_order_relaxed);
+    in.unpack = unpack;
     in.max_rows_per_launch = g_max_rows_per_launch.load(std::memory_order_relaxed);
     in.max_words_per_run = g_max_words_per_run.load(std::memory_order_relaxed);
     std::vector<Launch> launches;
@@ -278,6 +281,11 @@ int tp_set_override(const char* key, const char* value) {
         default: return kErrArg;
         }
         g_max_word_log2.store(log2);
+        return kSuccess;
+    }
+    if (!std::strcmp(key, "nt")) {
+        if (v < -1 || v > 3) return kErrArg;
+        g_nt.store(static_cast<int>(v));
         return kSuccess;
     }
     if (!std::strcmp(key, "check_buffers")) {

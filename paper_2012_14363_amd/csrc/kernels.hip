@@ -26,30 +26,42 @@ namespace tp {
 
 namespace {
 
+// Memory accesses with a streaming hint.  Every byte is touched once, so loads and
+// stores can carry the non-temporal bit (`nt`): the data then does not displace
+// other lines in L2 / Infinity Cache.  NT bit 0: loads, bit 1: stores.
+template <int NT>
 struct DeviceMem {
     template <class W>
     __device__ __forceinline__ W load(const char* p) const {
-        return *reinterpret_cast<const W*>(p);
+        if constexpr (NT & 1) return __builtin_nontemporal_load(reinterpret_cast<const W*>(p));
+        else return *reinterpret_cast<const W*>(p);
     }
     template <class W>
     __device__ __forceinline__ void store(char* p, const W& v) const {
-        *reinterpret_cast<W*>(p) = v;
+        if constexpr (NT & 2) __builtin_nontemporal_store(v, reinterpret_cast<W*>(p));
+        else *reinterpret_cast<W*>(p) = v;
     }
 };
 
-template <int WLOG2, int UX, int UR, bool UNPACK, int NRD>
+template <int WLOG2, int UX, int UR, bool UNPACK, int NRD, int NT>
 __global__ void __launch_bounds__(kBlockThreads) tile_kernel(const KParams p) {
-    tile_thread<WLOG2, UX, UR, UNPACK, NRD>(p, blockIdx.x, threadIdx.x, DeviceMem{});
+    tile_thread<WLOG2, UX, UR, UNPACK, NRD>(p, blockIdx.x, threadIdx.x, DeviceMem<NT>{});
 }
 
 using KernelFn = void (*)(const KParams);
 
 template <bool UNPACK>
 struct PickKernel {
+    int nt = 0;
     KernelFn fn = nullptr;
     template <int WLOG2, int UX, int UR, int NRD>
     void operator()() {
-        fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD>;
+        switch (nt) {
+        case 0: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 0>; break;
+        case 1: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 1>; break;
+        case 2: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 2>; break;
+        default: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 3>; break;
+        }
     }
 };
 
@@ -60,9 +72,11 @@ hipError_t enqueue(const Launch& l, bool unpack, hipStream_t stream) {
     KernelFn fn = nullptr;
     if (unpack) {
         PickKernel<true> pick;
+        pick.nt = l.nt;
         if (dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, pick)) fn = pick.fn;
     } else {
         PickKernel<false> pick;
+        pick.nt = l.nt;
         if (dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, pick)) fn = pick.fn;
     }
     if (!fn || l.nblocks == 0) return hipErrorInvalidValue;

@@ -65,6 +65,7 @@ struct Splitter {
         }
         p.nrows = static_cast<uint32_t>(rows);
         choose_tile(p.n0, &l);
+        l.nt = in.nt >= 0 ? in.nt : 3;
         const uint32_t bx = 1u << p.bx_log2;
         const uint32_t br = kBlockThreads >> p.bx_log2;
         p.nxc = (p.n0 + bx * l.ux - 1) / (bx * l.ux);
@@ -154,8 +155,8 @@ std::string describe(const std::vector<Launch>& launches) {
     std::string text;
     char line[256];
     for (const Launch& l : launches) {
-        std::snprintf(line, sizeof line, "tile W=%d ux=%d ur=%d bx=%u n0=%u rows=%u nrd=%u blocks=%u\n",
-                      1 << l.word_log2, l.ux, l.ur, 1u << l.p.bx_log2, l.p.n0, l.p.nrows, l.p.nrd, l.nblocks);
+        std::snprintf(line, sizeof line, "tile W=%d ux=%d ur=%d nt=%d bx=%u n0=%u rows=%u nrd=%u blocks=%u\n",
+                      1 << l.word_log2, l.ux, l.ur, l.nt, 1u << l.p.bx_log2, l.p.n0, l.p.nrows, l.p.nrd, l.nblocks);
         text += line;
     }
     return text;

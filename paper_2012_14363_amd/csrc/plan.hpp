@@ -40,6 +40,7 @@ struct Launch {
     int word_log2 = 0;  // W = 1 << word_log2 bytes per lane access
     int ux = 1;         // words per thread along the run
     int ur = 1;         // rows per thread
+    int nt = 3;         // streaming hints: bit 0 = non-temporal loads, bit 1 = non-temporal stores
     uint32_t nblocks = 0;
 };
 
@@ -50,6 +51,8 @@ struct PlanInput {
     const char* typed = nullptr;   // origin of object 0 in the typed buffer
     char* packed = nullptr;        // contiguous buffer + position
     int max_word_log2 = 4;   // override: cap on the access width
+    int nt = -1;             // override: streaming hints (-1 = planner's choice)
+    bool unpack = false;
     int64_t max_rows_per_launch = int64_t{1} << 30;   // tests lower these to force splitting
     int64_t max_words_per_run = int64_t{1} << 30;
 };

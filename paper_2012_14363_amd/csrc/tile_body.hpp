@@ -11,9 +11,12 @@
 
 namespace tp {
 
-struct alignas(16) Word16 {
-    uint32_t v[4];
-};
+// 16-byte access word: a native vector type so one global_load/store_dwordx4 moves it.
+#if defined(__clang__)
+typedef uint32_t Word16 __attribute__((ext_vector_type(4)));
+#else
+typedef uint32_t Word16 __attribute__((vector_size(16)));
+#endif
 
 template <int LOG2>
 struct WordOf;
