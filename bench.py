@@ -202,6 +202,7 @@ def main():
         out["cpu_baseline"] = cpu_baseline(W, np)
     if not args.no_extras:
         out["extras"] = extras(W, tp, torch, np, dev, stream)
+        out["other_workloads"] = other_workloads(W, tp, torch, arena, dev, stream)
     print(json.dumps(out))
 
 
@@ -301,6 +302,162 @@ def extras(W, tp, torch, np, dev, stream):
         q1, q2, q3 = ts[len(ts) // 4], ts[len(ts) // 2], ts[3 * len(ts) // 4]
         rows.append({"family": family, "construct_commit_trimean_us": round((q1 + 2 * q2 + q3) / 4 * 1e6, 2)})
     res["canonicalize_us_per_type_via_python_binding"] = rows
+    return res
+
+
+def other_workloads(W, tp, torch, arena, dev, stream):
+    """The remaining workloads, timed the same way (HIP events on the launch stream, median), with the
+    typed side taken from regions of the resident arena that rotate between repetitions so that no
+    repetition finds its lines in the 256 MiB Infinity Cache.  Reported, not part of `value`."""
+    res = {}
+    GiB = 1 << 30
+
+    def median_event_us(fn, reps):
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+        for k, (a, b) in enumerate(ev):
+            a.record(stream)
+            fn(k)
+            b.record(stream)
+        torch.cuda.synchronize()
+        ts = sorted(a.elapsed_time(b) for a, b in ev)
+        return ts[len(ts) // 2] * 1e3
+
+    def median_wall_us(fn, reps):
+        ts = []
+        for k in range(reps):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            fn(k)
+            ts.append(time.perf_counter() - t0)
+        ts.sort()
+        return ts[len(ts) // 2] * 1e6
+
+    # ---- 3D sweep at 1 MiB packed: latency regime (launch + kernel + synchronize per call)
+    rows = []
+    out1 = [torch.zeros(1 << 20, dtype=torch.uint8, device=dev) for _ in range(8)]
+    for p in W.configs.cfg2_sweep(1 << 20):
+        h = tp.type_from_recipe(p["recipe"])
+        span = p["alloc_bytes"]
+        nreg = max(1, min(16, (8 * GiB) // span))
+        pk = median_wall_us(lambda k: tp.pack(arena.data_ptr() + (k % nreg) * span, 1, h, out1[k % 8], 1 << 20, 0, stream), 30)
+        up = median_wall_us(lambda k: tp.unpack(out1[k % 8], 1 << 20, 0, arena.data_ptr() + (k % nreg) * span, 1, h, stream), 30)
+        pk_ev = median_event_us(lambda k: tp.pack_async(arena.data_ptr() + (k % nreg) * span, 1, h, out1[k % 8], 1 << 20, 0, stream), 30)
+        up_ev = median_event_us(lambda k: tp.unpack_async(out1[k % 8], 1 << 20, 0, arena.data_ptr() + (k % nreg) * span, 1, h, stream), 30)
+        rows.append({"a": list(p["a"]), "pack_sync_call_us": round(pk, 1), "unpack_sync_call_us": round(up, 1),
+                     "pack_event_us": round(pk_ev, 1), "unpack_event_us": round(up_ev, 1),
+                     "pack_gbs_event": round(2 * (1 << 20) / pk_ev / 1e3, 1)})
+    res["sweep_1MiB"] = rows
+
+    # ---- halo: 26 regions of a 512^3 float64 grid, ghost width 3
+    c3 = W.configs.cfg3()
+    send = [tp.type_from_recipe(r) for r in c3["send"]]
+    ghost = [tp.type_from_recipe(r) for r in c3["ghost_for_send"]]
+    sizes = [tp.type_size(h) for h in send]
+    total = sum(sizes)
+    bufs = [torch.zeros(total, dtype=torch.uint8, device=dev) for _ in range(8)]
+    grid_at = lambda k: arena.data_ptr() + (k % 8) * GiB   # noqa: E731
+
+    def halo(k, types, unpack, sync_each):
+        pos = 0
+        for h in types:
+            if unpack:
+                f = tp.unpack if sync_each else tp.unpack_async
+                pos = f(bufs[k % 8], total, pos, grid_at(k), 1, h, stream)
+            else:
+                f = tp.pack if sync_each else tp.pack_async
+                pos = f(grid_at(k), 1, h, bufs[k % 8], total, pos, stream)
+        if not sync_each:
+            stream.synchronize()
+    halo_res = {"packed_bytes": total}
+    for name, types, unpack in (("pack", send, False), ("unpack", ghost, True)):
+        t_sync = median_wall_us(lambda k: halo(k, types, unpack, True), 12)
+        t_async = median_wall_us(lambda k: halo(k, types, unpack, False), 12)
+        halo_res[name] = {"26_sync_calls_us": round(t_sync, 1), "26_async_calls_one_sync_us": round(t_async, 1),
+                          "gbs_async": round(2 * total / t_async / 1e3, 1)}
+        # the same 26 requests as one batched launch
+        def batched(k, types=types, unpack=unpack):
+            b = batches[(name, k % 8)]
+            if unpack:
+                tp.unpack_batch_async(bufs[k % 8], total, 0, b, stream)
+            else:
+                tp.pack_batch_async(b, bufs[k % 8], total, 0, stream)
+        batches = {(name, j): tp.Batch([grid_at(j)] * 26, [1] * 26, types) for j in range(8)}
+        t_b_ev = median_event_us(batched, 16)
+        t_b_wall = median_wall_us(lambda k: (batched(k), stream.synchronize()), 12)
+        halo_res[name].update({"batched_one_launch_event_us": round(t_b_ev, 1),
+                               "batched_one_launch_call_and_sync_us": round(t_b_wall, 1),
+                               "gbs_batched_event": round(2 * total / t_b_ev / 1e3, 1),
+                               "gbs_batched_call_and_sync": round(2 * total / t_b_wall / 1e3, 1)})
+    # per class: one x-face (24-byte runs), one y-face, one z-face (4048-byte runs)
+    dirs = c3["directions"]
+    for label, d in (("x_face", (0, 0, -1)), ("y_face", (0, -1, 0)), ("z_face", (-1, 0, 0))):
+        i = dirs.index(d)
+        h, g = send[i], ghost[i]
+        n = sizes[i]
+        pk = median_event_us(lambda k: tp.pack_async(grid_at(k), 1, h, bufs[k % 8], total, 0, stream), 16)
+        plan = tp.last_plan().strip()
+        up = median_event_us(lambda k: tp.unpack_async(bufs[k % 8], total, 0, grid_at(k), 1, g, stream), 16)
+        halo_res[label] = {"bytes": n, "pack_us": round(pk, 1), "pack_gbs": round(2 * n / pk / 1e3, 1),
+                           "unpack_us": round(up, 1), "unpack_gbs": round(2 * n / up / 1e3, 1), "plan": plan}
+    res["halo_26_regions"] = halo_res
+    del bufs
+
+    # ---- tiny runs: 2^24 runs of bl bytes at 64-byte stride (1 GiB footprint)
+    rows = []
+    outs = [torch.zeros(8 << 24, dtype=torch.uint8, device=dev) for _ in range(4)]
+    for bl in W.configs.CFG4_BLOCKLENGTHS:
+        p = W.configs.cfg4_point(bl)
+        h = tp.type_from_recipe(p["recipe"])
+        n = p["packed_bytes"]
+        for off in (0, 3):
+            src = lambda k: arena.data_ptr() + (k % 8) * 2 * GiB + off   # noqa: E731
+            pk = median_event_us(lambda k: tp.pack_async(src(k), 1, h, outs[k % 4], n, 0, stream), 12)
+            plan = tp.last_plan().strip()
+            up = median_event_us(lambda k: tp.unpack_async(outs[k % 4], n, 0, src(k), 1, h, stream), 12)
+            rows.append({"blocklength": bl, "offset": off, "pack_us": round(pk, 1), "unpack_us": round(up, 1),
+                         "pack_gbs": round(2 * n / pk / 1e3, 1), "unpack_gbs": round(2 * n / up / 1e3, 1),
+                         "pack_footprint_gbs": round((GiB + n) / pk / 1e3, 1), "plan": plan})
+    res["tiny_runs_2p24_stride64"] = rows
+    del outs
+
+    # ---- nested 4-level type, 1000 objects of 2 MiB packed
+    c5 = W.configs.cfg5()
+    h = tp.type_from_recipe(c5["recipe"])
+    ex, size, nobj = tp.type_get_extent(h)[1], tp.type_size(h), c5["objects"]
+    out = torch.zeros(nobj * size, dtype=torch.uint8, device=dev)
+    base = lambda k: arena.data_ptr() + (k % 4) * 10 * GiB   # noqa: E731
+    one = median_event_us(lambda k: tp.pack_async(base(k), nobj, h, out, nobj * size, 0, stream), 8)
+    plan = tp.last_plan().strip()
+
+    def many_async(k):
+        pos = 0
+        for i in range(nobj):
+            pos = tp.pack_async(base(k) + i * ex, 1, h, out, nobj * size, pos, stream)
+        stream.synchronize()
+
+    def many_sync(k):
+        pos = 0
+        for i in range(100):
+            pos = tp.pack(base(k) + i * ex, 1, h, out, nobj * size, pos, stream)
+    t_async = median_wall_us(many_async, 5)
+    t_sync = median_wall_us(many_sync, 5)
+    nested = {"objects": nobj, "packed_bytes_per_object": size, "plan": plan,
+              "one_call_incount_1000_us": round(one, 1), "one_call_us_per_object": round(one / nobj, 3),
+              "one_call_gbs": round(2 * nobj * size / one / 1e3, 1),
+              "1000_async_calls_one_sync_us_per_object": round(t_async / nobj, 2),
+              "1000_async_calls_gbs": round(2 * nobj * size / t_async / 1e3, 1),
+              "sync_call_us_per_object": round(t_sync / 100, 2)}
+    bb = [tp.Batch([base(j) + i * ex for i in range(nobj)], [1] * nobj, [h] * nobj) for j in range(4)]
+    t_batch = median_wall_us(lambda k: (tp.pack_batch_async(bb[k % 4], out, nobj * size, 0, stream),
+                                        stream.synchronize()), 5)
+    nested["1000_objects_batched_us_per_object"] = round(t_batch / nobj, 3)
+    nested["1000_objects_batched_gbs"] = round(2 * nobj * size / t_batch / 1e3, 1)
+    npin = 128
+    pinned = torch.zeros(npin * size, dtype=torch.uint8).pin_memory()
+    t_pin = median_wall_us(lambda k: tp.pack(base(k), npin, h, pinned, npin * size, 0, stream), 5)
+    nested["zero_copy_pinned_host"] = {"objects": npin, "us_per_object": round(t_pin / npin, 2),
+                                       "packed_gbs_over_pcie": round(npin * size / t_pin / 1e3, 1)}
+    res["nested_4level"] = nested
     return res
 
 

@@ -134,6 +134,25 @@ int tp_pack_async(const void *inbuf, int incount, tp_type t, void *outbuf, int64
 int tp_unpack_async(const void *inbuf, int64_t insize, int64_t *position, void *outbuf, int outcount, tp_type t,
                     void *hip_stream);
 
+/* ---- batched pack / unpack -------------------------------------------------------------------
+ * n requests that share one contiguous buffer and one running position, enqueued as few kernel
+ * launches as possible (one launch carries up to 40 requests of *different* datatypes; the paper,
+ * Sec. 7, fuses only copies of one datatype).  The result is exactly that of n consecutive
+ * tp_pack (tp_unpack) calls in order i = 0..n-1: request i moves incounts[i] objects of types[i]
+ * whose typed buffer is inbufs[i] (outbufs[i]).  All requests are validated first: on any error
+ * nothing is enqueued and *position is unchanged.  Same memory rules as tp_pack/tp_unpack; for
+ * unpack the requests' type maps must not overlap each other.  The plain forms synchronize the
+ * stream; the *_async forms only enqueue.
+ */
+int tp_pack_batch(int n, const void *const inbufs[], const int incounts[], const tp_type types[], void *outbuf,
+                  int64_t outsize, int64_t *position, void *hip_stream);
+int tp_unpack_batch(int n, const void *inbuf, int64_t insize, int64_t *position, void *const outbufs[],
+                    const int outcounts[], const tp_type types[], void *hip_stream);
+int tp_pack_batch_async(int n, const void *const inbufs[], const int incounts[], const tp_type types[], void *outbuf,
+                        int64_t outsize, int64_t *position, void *hip_stream);
+int tp_unpack_batch_async(int n, const void *inbuf, int64_t insize, int64_t *position, void *const outbufs[],
+                          const int outcounts[], const tp_type types[], void *hip_stream);
+
 /* ---- introspection for tests and ablations ------------------------------------------------------
  * tp_type_get_strided_block: the canonical form of a committed type (Sec. 3.3): *ndims dimensions,
  * counts[0] contiguous bytes with strides[0] == 1, dimension d+1 repeats dimension d counts[d+1]

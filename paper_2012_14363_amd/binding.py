@@ -30,6 +30,7 @@ EXPORTS = (
     "tp_type_contiguous", "tp_type_vector", "tp_type_create_hvector", "tp_type_create_subarray",
     "tp_type_commit", "tp_type_free", "tp_type_size", "tp_type_get_extent", "tp_pack_size",
     "tp_pack", "tp_unpack", "tp_pack_async", "tp_unpack_async",
+    "tp_pack_batch", "tp_unpack_batch", "tp_pack_batch_async", "tp_unpack_batch_async",
     "tp_type_get_strided_block", "tp_set_override", "tp_last_plan", "tp_error_string",
 )
 
@@ -61,6 +62,7 @@ def lib() -> ctypes.CDLL:
         L = ctypes.CDLL(LIB_PATH)
         i32, i64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
         pi32, pi64, pint = ctypes.POINTER(i32), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_int)
+        pvp = ctypes.POINTER(vp)
         sig = {
             "tp_type_contiguous": [ctypes.c_int, i32, pi32],
             "tp_type_vector": [ctypes.c_int, ctypes.c_int, ctypes.c_int, i32, pi32],
@@ -75,6 +77,10 @@ def lib() -> ctypes.CDLL:
             "tp_unpack": [vp, i64, pi64, vp, ctypes.c_int, i32, vp],
             "tp_pack_async": [vp, ctypes.c_int, i32, vp, i64, pi64, vp],
             "tp_unpack_async": [vp, i64, pi64, vp, ctypes.c_int, i32, vp],
+            "tp_pack_batch": [ctypes.c_int, pvp, pint, pi32, vp, i64, pi64, vp],
+            "tp_unpack_batch": [ctypes.c_int, vp, i64, pi64, pvp, pint, pi32, vp],
+            "tp_pack_batch_async": [ctypes.c_int, pvp, pint, pi32, vp, i64, pi64, vp],
+            "tp_unpack_batch_async": [ctypes.c_int, vp, i64, pi64, pvp, pint, pi32, vp],
             "tp_type_get_strided_block": [i32, pint, pi64, pi64, pi64],
             "tp_set_override": [ctypes.c_char_p, ctypes.c_char_p],
         }
@@ -220,6 +226,49 @@ def unpack(inbuf, insize: int, position: int, outbuf, outcount: int, t: int, str
 
 def unpack_async(inbuf, insize: int, position: int, outbuf, outcount: int, t: int, stream=None) -> int:
     return _transfer("tp_unpack_async", inbuf, (insize, outbuf, outcount, t), position, stream)
+
+
+class Batch:
+    """Marshalled argument arrays of a batched call, reusable across calls (the arrays are built once)."""
+
+    def __init__(self, typed_bufs, counts, types):
+        n = len(types)
+        assert len(typed_bufs) == len(counts) == n
+        self.n = n
+        self.ptrs = (ctypes.c_void_p * n)(*[_ptr(b) for b in typed_bufs])
+        self.counts = (ctypes.c_int * n)(*counts)
+        self.types = (ctypes.c_int32 * n)(*types)
+
+
+def _batch(fn_name, batch, packed, packed_size, position, stream):
+    pos = ctypes.c_int64(position)
+    fn = getattr(lib(), fn_name)
+    if "unpack" in fn_name:
+        rc = fn(batch.n, _ptr(packed), packed_size, ctypes.byref(pos), batch.ptrs, batch.counts, batch.types,
+                _stream(stream))
+    else:
+        rc = fn(batch.n, batch.ptrs, batch.counts, batch.types, _ptr(packed), packed_size, ctypes.byref(pos),
+                _stream(stream))
+    _check(rc, fn_name)
+    return pos.value
+
+
+def pack_batch(batch: Batch, outbuf, outsize: int, position: int, stream=None) -> int:
+    """tp_pack_batch; returns the new position."""
+    return _batch("tp_pack_batch", batch, outbuf, outsize, position, stream)
+
+
+def pack_batch_async(batch: Batch, outbuf, outsize: int, position: int, stream=None) -> int:
+    return _batch("tp_pack_batch_async", batch, outbuf, outsize, position, stream)
+
+
+def unpack_batch(inbuf, insize: int, position: int, batch: Batch, stream=None) -> int:
+    """tp_unpack_batch; returns the new position."""
+    return _batch("tp_unpack_batch", batch, inbuf, insize, position, stream)
+
+
+def unpack_batch_async(inbuf, insize: int, position: int, batch: Batch, stream=None) -> int:
+    return _batch("tp_unpack_batch_async", batch, inbuf, insize, position, stream)
 
 
 # ------------------------------------------------------------------ recipes -> handles

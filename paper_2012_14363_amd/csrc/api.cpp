@@ -95,43 +95,87 @@ int resolve_pointer(const void* ptr, bool allow_host, const char** device_view) 
     }
 }
 
-int transfer(bool unpack, const void* typed_buf, int64_t count, tp_type t, const void* packed_buf,
-             int64_t packed_size, int64_t* position, void* hip_stream, bool synchronize) {
-    if (!position) return kErrArg;
-    const TypePtr node = committed_node(t);
-    if (!node) return kErrType;
-    if (count < 0) return kErrCount;
-    if (*position < 0 || packed_size < 0) return kErrArg;
-    int64_t bytes;
-    if (__builtin_mul_overflow(count, node->size, &bytes)) return kErrRange;
-    if (bytes > packed_size - *position) return kErrTruncate;
-    t_last_plan.clear();
-    if (bytes == 0) return kSuccess;
-    if (!typed_buf || !packed_buf) return kErrBuffer;
+// The contiguous buffer of a call, resolved to a GPU-usable address on first need (after the
+// request has passed the checks that need no device).
+struct PackedSide {
+    const void* raw = nullptr;
+    const char* view = nullptr;
+    bool resolved = false;
+    int resolve() {
+        if (resolved) return kSuccess;
+        const int rc = resolve_pointer(raw, true, &view);
+        resolved = rc == kSuccess;
+        return rc;
+    }
+};
 
+// Checks of one pack/unpack request that need no device: handle, count, fit, null buffers.
+// On success *bytes is what the request moves and *node its datatype.
+int check_request(const void* typed_buf, int64_t count, tp_type t, const void* packed_buf, int64_t packed_size,
+                  int64_t position, TypePtr* node, int64_t* bytes) {
+    *node = committed_node(t);
+    if (!*node) return kErrType;
+    if (count < 0) return kErrCount;
+    if (__builtin_mul_overflow(count, (*node)->size, bytes)) return kErrRange;
+    if (*bytes > packed_size - position) return kErrTruncate;
+    if (*bytes > 0 && (!typed_buf || !packed_buf)) return kErrBuffer;
+    return kSuccess;
+}
+
+// Resolves the buffers of a checked request and appends its planned launches to `launches`.
+int plan_request(bool unpack, const TypeNode& node, const void* typed_buf, int64_t count, PackedSide* packed,
+                 int64_t position, std::vector<Launch>* launches) {
     const char* typed_view = nullptr;
-    const char* packed_view = nullptr;
     int rc = resolve_pointer(typed_buf, false, &typed_view);
     if (rc != kSuccess) return rc;
-    rc = resolve_pointer(packed_buf, true, &packed_view);
+    rc = packed->resolve();
     if (rc != kSuccess) return rc;
-
     PlanInput in;
-    in.block = node->block;
-    in.extent = node->extent();
+    in.block = node.block;
+    in.extent = node.extent();
     in.count = count;
     in.typed = typed_view;
-    in.packed = const_cast<char*>(packed_view) + *position;
+    in.packed = const_cast<char*>(packed->view) + position;
     in.max_word_log2 = g_max_word_log2.load(std::memory_order_relaxed);
     in.nt = g_nt.load(std::memory_order_relaxed);
     in.unpack = unpack;
     in.max_rows_per_launch = g_max_rows_per_launch.load(std::memory_order_relaxed);
     in.max_words_per_run = g_max_words_per_run.load(std::memory_order_relaxed);
-    std::vector<Launch> launches;
-    rc = plan_launches(in, &launches);
+    std::vector<Launch> mine;
+    rc = plan_launches(in, &mine);
     if (rc != kSuccess) return rc;
-    t_last_plan = describe(launches);
+    launches->insert(launches->end(), mine.begin(), mine.end());
+    return kSuccess;
+}
 
+int finish(hipStream_t stream, bool synchronize) {
+    if (!synchronize) return kSuccess;
+    const hipError_t e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) {
+        t_last_hip_error = hipGetErrorString(e);
+        return kErrOther;
+    }
+    return kSuccess;
+}
+
+int transfer(bool unpack, const void* typed_buf, int64_t count, tp_type t, const void* packed_buf,
+             int64_t packed_size, int64_t* position, void* hip_stream, bool synchronize) {
+    if (!position) return kErrArg;
+    if (*position < 0 || packed_size < 0) return kErrArg;
+    t_last_plan.clear();
+    PackedSide packed;
+    packed.raw = packed_buf;
+    TypePtr node;
+    int64_t bytes = 0;
+    int rc = check_request(typed_buf, count, t, packed_buf, packed_size, *position, &node, &bytes);
+    if (rc != kSuccess) return rc;
+    std::vector<Launch> launches;
+    if (bytes > 0) {
+        rc = plan_request(unpack, *node, typed_buf, count, &packed, *position, &launches);
+        if (rc != kSuccess) return rc;
+    }
+    const int64_t pos = *position + bytes;
+    t_last_plan = describe(launches);
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     for (const Launch& l : launches) {
         const hipError_t e = enqueue(l, unpack, stream);
@@ -140,14 +184,65 @@ int transfer(bool unpack, const void* typed_buf, int64_t count, tp_type t, const
             return kErrOther;
         }
     }
-    if (synchronize) {
-        const hipError_t e = hipStreamSynchronize(stream);
+    if (!launches.empty()) {
+        rc = finish(stream, synchronize);
+        if (rc != kSuccess) return rc;
+    }
+    *position = pos;
+    return kSuccess;
+}
+
+// n pack (or unpack) requests sharing one contiguous buffer and one running position, enqueued
+// as few launches as possible.  All requests are validated and planned before anything is enqueued.
+int transfer_batch(bool unpack, int n, const void* const* typed_bufs, const int* counts, const tp_type* types,
+                   const void* packed_buf, int64_t packed_size, int64_t* position, void* hip_stream,
+                   bool synchronize) {
+    if (!position || n < 0) return kErrArg;
+    if (n > 0 && (!typed_bufs || !counts || !types)) return kErrArg;
+    if (*position < 0 || packed_size < 0) return kErrArg;
+    t_last_plan.clear();
+    PackedSide packed;
+    packed.raw = packed_buf;
+    int64_t pos = *position;
+    std::vector<TypePtr> nodes(static_cast<size_t>(n));
+    std::vector<int64_t> offsets(static_cast<size_t>(n)), sizes(static_cast<size_t>(n));
+    for (int i = 0; i < n; ++i) {  // every check that needs no device, for all requests, first
+        const int rc = check_request(typed_bufs[i], counts[i], types[i], packed_buf, packed_size, pos, &nodes[i],
+                                     &sizes[i]);
+        if (rc != kSuccess) return rc;
+        offsets[i] = pos;
+        pos += sizes[i];
+    }
+    std::vector<Launch> launches;
+    for (int i = 0; i < n; ++i) {
+        if (sizes[i] == 0) continue;
+        const int rc = plan_request(unpack, *nodes[i], typed_bufs[i], counts[i], &packed, offsets[i], &launches);
+        if (rc != kSuccess) return rc;
+    }
+    std::vector<BatchParams> batches;
+    std::vector<Launch> singles;
+    make_batches(launches, &batches, &singles);
+    t_last_plan = describe(batches) + describe(singles);
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    for (const BatchParams& b : batches) {
+        const hipError_t e = enqueue_batch(b, unpack, stream);
         if (e != hipSuccess) {
             t_last_hip_error = hipGetErrorString(e);
             return kErrOther;
         }
     }
-    *position += bytes;
+    for (const Launch& l : singles) {
+        const hipError_t e = enqueue(l, unpack, stream);
+        if (e != hipSuccess) {
+            t_last_hip_error = hipGetErrorString(e);
+            return kErrOther;
+        }
+    }
+    if (!launches.empty()) {
+        const int rc = finish(stream, synchronize);
+        if (rc != kSuccess) return rc;
+    }
+    *position = pos;
     return kSuccess;
 }
 
@@ -248,6 +343,26 @@ int tp_pack_async(const void* inbuf, int incount, tp_type t, void* outbuf, int64
 int tp_unpack_async(const void* inbuf, int64_t insize, int64_t* position, void* outbuf, int outcount, tp_type t,
                     void* hip_stream) {
     return transfer(true, outbuf, outcount, t, inbuf, insize, position, hip_stream, false);
+}
+
+int tp_pack_batch(int n, const void* const inbufs[], const int incounts[], const tp_type types[], void* outbuf,
+                  int64_t outsize, int64_t* position, void* hip_stream) {
+    return transfer_batch(false, n, inbufs, incounts, types, outbuf, outsize, position, hip_stream, true);
+}
+
+int tp_unpack_batch(int n, const void* inbuf, int64_t insize, int64_t* position, void* const outbufs[],
+                    const int outcounts[], const tp_type types[], void* hip_stream) {
+    return transfer_batch(true, n, outbufs, outcounts, types, inbuf, insize, position, hip_stream, true);
+}
+
+int tp_pack_batch_async(int n, const void* const inbufs[], const int incounts[], const tp_type types[], void* outbuf,
+                        int64_t outsize, int64_t* position, void* hip_stream) {
+    return transfer_batch(false, n, inbufs, incounts, types, outbuf, outsize, position, hip_stream, false);
+}
+
+int tp_unpack_batch_async(int n, const void* inbuf, int64_t insize, int64_t* position, void* const outbufs[],
+                          const int outcounts[], const tp_type types[], void* hip_stream) {
+    return transfer_batch(true, n, outbufs, outcounts, types, inbuf, insize, position, hip_stream, false);
 }
 
 int tp_type_get_strided_block(tp_type t, int* ndims, int64_t* start, int64_t counts[], int64_t strides[]) {

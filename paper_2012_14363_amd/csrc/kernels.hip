@@ -48,6 +48,15 @@ __global__ void __launch_bounds__(kBlockThreads) tile_kernel(const KParams p) {
     tile_thread<WLOG2, UX, UR, UNPACK, NRD>(p, blockIdx.x, threadIdx.x, DeviceMem<NT>{});
 }
 
+// Many planned launches, of different datatypes, as one grid: a workgroup looks up
+// the descriptor that owns it (binary search over at most 40 block ranges, scalar)
+// and runs the same tile body.  Saves one launch per datatype where launches are
+// short, e.g. the 26 regions of a halo exchange.
+template <bool UNPACK>
+__global__ void __launch_bounds__(kBlockThreads) batch_kernel(const BatchParams b) {
+    batch_thread<UNPACK>(b, blockIdx.x, threadIdx.x, DeviceMem<3>{});
+}
+
 using KernelFn = void (*)(const KParams);
 
 template <bool UNPACK>
@@ -81,6 +90,13 @@ hipError_t enqueue(const Launch& l, bool unpack, hipStream_t stream) {
     }
     if (!fn || l.nblocks == 0) return hipErrorInvalidValue;
     hipLaunchKernelGGL(fn, dim3(l.nblocks), dim3(kBlockThreads), 0, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t enqueue_batch(const BatchParams& b, bool unpack, hipStream_t stream) {
+    if (b.n == 0 || b.nblocks == 0) return hipErrorInvalidValue;
+    if (unpack) hipLaunchKernelGGL(batch_kernel<true>, dim3(b.nblocks), dim3(kBlockThreads), 0, stream, b);
+    else hipLaunchKernelGGL(batch_kernel<false>, dim3(b.nblocks), dim3(kBlockThreads), 0, stream, b);
     return hipGetLastError();
 }
 

@@ -10,4 +10,7 @@ namespace tp {
 // Enqueues one planned launch on `stream`.  Returns hipSuccess or the launch error.
 hipError_t enqueue(const Launch& launch, bool unpack, hipStream_t stream);
 
+// Enqueues one batched launch (see plan.hpp: BatchParams).
+hipError_t enqueue_batch(const BatchParams& batch, bool unpack, hipStream_t stream);
+
 }  // namespace tp

@@ -60,6 +60,43 @@ struct PlanInput {
 // Fills `out` (cleared first).  Returns a TP_* status.
 int plan_launches(const PlanInput& in, std::vector<Launch>* out);
 
+// ---- batched launches: many planned launches (of different datatypes) in one grid ----------
+// The descriptors still travel in the kernel-argument segment (4 KiB at most), so each is
+// packed into 96 bytes and limited to kBatchRowDims row dimensions.
+constexpr int kBatchRowDims = 3;
+constexpr int kBatchMax = 40;
+
+struct BatchDesc {
+    const char* strided;
+    char* packed;
+    int64_t row_pitch;
+    int64_t rstride[kBatchRowDims];
+    uint32_t rcount[kBatchRowDims];
+    uint32_t rmul[kBatchRowDims];
+    uint32_t n0, nrows, nxc, xc_mul;
+    uint8_t rshift[kBatchRowDims];
+    uint8_t xc_shift, bx_log2, word_log2;
+    uint8_t tile;  // 0: (ux,ur) = (1,4); 1: (2,2); 2: (4,1)
+    uint8_t nrd;   // 1..kBatchRowDims
+};
+static_assert(sizeof(BatchDesc) == 96, "BatchDesc must stay 96 bytes");
+
+struct BatchParams {
+    uint32_t n = 0;                    // descriptors in use
+    uint32_t nblocks = 0;              // == block_end[n - 1]
+    uint32_t block_end[kBatchMax] = {};  // descriptor j owns workgroups [block_end[j-1], block_end[j])
+    BatchDesc d[kBatchMax];
+};
+static_assert(sizeof(BatchParams) <= 4096, "BatchParams must fit the kernel-argument segment");
+
+// True if a launch can ride in a batch (few enough row dimensions).
+bool batchable(const Launch& l);
+// Groups launches into batches of at most kBatchMax descriptors, in order.  Launches that are
+// not batchable are appended to `singles`.
+void make_batches(const std::vector<Launch>& launches, std::vector<BatchParams>* batches,
+                  std::vector<Launch>* singles);
+std::string describe(const std::vector<BatchParams>& batches);
+
 // One line per launch, for tp_last_plan().
 std::string describe(const std::vector<Launch>& launches);
 

@@ -33,8 +33,8 @@ struct WordOf<4> { using type = Word16; };
 
 // Byte offset of row r in the typed buffer.  NRD > 0: that many row dimensions,
 // unrolled; NRD == 0: p.nrd (>= 1) of them, looped.
-template <int NRD>
-TP_HD inline int64_t row_offset(uint32_t r, const KParams& p) {
+template <int NRD, class P>
+TP_HD inline int64_t row_offset(uint32_t r, const P& p) {
     int64_t off = 0;
     const int n = NRD > 0 ? NRD : static_cast<int>(p.nrd);
 #pragma unroll
@@ -51,8 +51,9 @@ TP_HD inline int64_t row_offset(uint32_t r, const KParams& p) {
 // Thread `tid` of workgroup `block`.  The workgroup is a flat tile of
 // bx = 1 << bx_log2 lanes along the run by 256/bx rows; this thread moves UX words
 // of each of UR rows.  `Mem` supplies load/store (plain accesses on the device).
-template <int WLOG2, int UX, int UR, bool UNPACK, int NRD, class Mem>
-TP_HD inline void tile_thread(const KParams& p, uint32_t block, uint32_t tid, Mem mem) {
+// `P` is KParams, or the register-resident SmallParams a batched launch unpacks.
+template <int WLOG2, int UX, int UR, bool UNPACK, int NRD, class P, class Mem>
+TP_HD inline void tile_thread(const P& p, uint32_t block, uint32_t tid, Mem mem) {
     using W = typename WordOf<WLOG2>::type;
     const uint32_t tx = tid & ((1u << p.bx_log2) - 1u);
     const uint32_t tr = tid >> p.bx_log2;
@@ -125,6 +126,88 @@ inline bool dispatch_variant(int word_log2, int ux, int ur, uint32_t nrd, F&& f)
     case 4: return by_tile(std::integral_constant<int, 4>{});
     default: return false;
     }
+}
+
+// ------------------------------------------------------------------ batched launches
+// One descriptor of a batched launch, unpacked from its compact kernel-argument
+// form into the field names tile_thread reads.  At most kBatchRowDims row
+// dimensions, all indexed with compile-time constants, so it lives in registers.
+struct SmallParams {
+    const char* strided;
+    char* packed;
+    int64_t row_pitch;
+    uint32_t n0, nrows, bx_log2, nxc, nrd;
+    FastDiv xc_div;
+    FastDiv rdiv[kBatchRowDims];
+    uint32_t rcount[kBatchRowDims];
+    int64_t rstride[kBatchRowDims];
+};
+
+TP_HD inline SmallParams unpack_desc(const BatchDesc& d) {
+    SmallParams p;
+    p.strided = d.strided;
+    p.packed = d.packed;
+    p.row_pitch = d.row_pitch;
+    p.n0 = d.n0;
+    p.nrows = d.nrows;
+    p.bx_log2 = d.bx_log2;
+    p.nxc = d.nxc;
+    p.nrd = d.nrd;
+    p.xc_div.mul = d.xc_mul;
+    p.xc_div.shift = d.xc_shift;
+    p.xc_div.divisor = d.nxc;
+    for (int k = 0; k < kBatchRowDims; ++k) {
+        p.rdiv[k].mul = d.rmul[k];
+        p.rdiv[k].shift = d.rshift[k];
+        p.rdiv[k].divisor = d.rcount[k];
+        p.rcount[k] = d.rcount[k];
+        p.rstride[k] = d.rstride[k];
+    }
+    return p;
+}
+
+// Index of the descriptor that owns workgroup `block`: the first j with block < block_end[j].
+TP_HD inline uint32_t find_desc(const BatchParams& b, uint32_t block) {
+    uint32_t lo = 0, hi = b.n - 1;
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (block < b.block_end[mid]) hi = mid; else lo = mid + 1;
+    }
+    return lo;
+}
+
+// Workgroup `block`, thread `tid` of a batched launch: find the descriptor, then run the
+// tile body of the variant it names (word width x tile x row dimensions, all unrolled).
+template <bool UNPACK, class Mem>
+TP_HD inline void batch_thread(const BatchParams& b, uint32_t block, uint32_t tid, Mem mem) {
+    const uint32_t j = find_desc(b, block);
+    const uint32_t first = j == 0 ? 0u : b.block_end[j - 1];
+    const SmallParams p = unpack_desc(b.d[j]);
+    const uint32_t local = block - first;
+    const uint32_t wl = b.d[j].word_log2, tile = b.d[j].tile, nrd = b.d[j].nrd;
+#define TP_BATCH_CASE(WL, X, R, N) tile_thread<WL, X, R, UNPACK, N>(p, local, tid, mem)
+#define TP_BATCH_NRD(WL, X, R)            \
+    do {                                  \
+        if (nrd <= 1) TP_BATCH_CASE(WL, X, R, 1);      \
+        else if (nrd == 2) TP_BATCH_CASE(WL, X, R, 2); \
+        else TP_BATCH_CASE(WL, X, R, 3);               \
+    } while (0)
+#define TP_BATCH_TILE(WL)                              \
+    do {                                               \
+        if (tile == 0) TP_BATCH_NRD(WL, 1, 4);         \
+        else if (tile == 1) TP_BATCH_NRD(WL, 2, 2);    \
+        else TP_BATCH_NRD(WL, 4, 1);                   \
+    } while (0)
+    switch (wl) {
+    case 0: TP_BATCH_TILE(0); break;
+    case 1: TP_BATCH_TILE(1); break;
+    case 2: TP_BATCH_TILE(2); break;
+    case 3: TP_BATCH_TILE(3); break;
+    default: TP_BATCH_TILE(4); break;
+    }
+#undef TP_BATCH_TILE
+#undef TP_BATCH_NRD
+#undef TP_BATCH_CASE
 }
 
 // A launch as the kernel sees it: a single row gets one dummy row dimension so the

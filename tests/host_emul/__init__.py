@@ -32,6 +32,10 @@ def _load():
         L.emul_transfer.argtypes = [ctypes.c_int, ctypes.c_int, i64, p64, p64, i64, i64, vp, i64, i64, vp, i64, i64,
                                     ctypes.c_int, i64, i64, vp, p64, ctypes.c_char_p, i64]
         L.emul_transfer.restype = ctypes.c_int
+        pint = ctypes.POINTER(ctypes.c_int)
+        L.emul_transfer_batch.argtypes = [ctypes.c_int, ctypes.c_int, pint, p64, p64, p64, p64, p64, p64, p64, vp, i64,
+                                          vp, i64, i64, vp, p64]
+        L.emul_transfer_batch.restype = ctypes.c_int
         _lib = L
     return _lib
 
@@ -55,3 +59,26 @@ def transfer(unpack, block, extent, count, typed, origin, packed, position, *, m
                                wc.ctypes.data if wc is not None else None, result, text, len(text))
     return {"rc": rc, "oob": result[0], "misaligned": result[1], "rewritten": result[2], "launches": result[3],
             "plan": text.value.decode(), "write_count": wc}
+
+
+def transfer_batch(unpack, requests, typed, packed, position, count_writes=True):
+    """Emulates tp_pack_batch / tp_unpack_batch.  `requests` = list of dicts with keys
+    block (start, counts, strides), extent, count, origin, size (bytes of one object)."""
+    n = len(requests)
+    ndims = (ctypes.c_int * n)(*[len(r["block"][1]) for r in requests])
+    starts = (ctypes.c_int64 * n)(*[r["block"][0] for r in requests])
+    counts = (ctypes.c_int64 * (16 * n))()
+    strides = (ctypes.c_int64 * (16 * n))()
+    for i, r in enumerate(requests):
+        for d, (c, s) in enumerate(zip(r["block"][1], r["block"][2])):
+            counts[16 * i + d], strides[16 * i + d] = c, s
+    arr = lambda key: (ctypes.c_int64 * n)(*[r[key] for r in requests])  # noqa: E731
+    dst = typed if unpack else packed
+    wc = np.zeros(dst.size, dtype=np.uint8) if count_writes else None
+    result = (ctypes.c_int64 * 5)()
+    rc = _load().emul_transfer_batch(int(unpack), n, ndims, starts, counts, strides, arr("extent"), arr("count"),
+                                     arr("origin"), arr("size"), typed.ctypes.data, typed.size,
+                                     packed.ctypes.data, packed.size, position,
+                                     wc.ctypes.data if wc is not None else None, result)
+    return {"rc": rc, "oob": result[0], "misaligned": result[1], "rewritten": result[2], "batches": result[3],
+            "singles": result[4], "write_count": wc}

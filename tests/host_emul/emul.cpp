@@ -124,4 +124,64 @@ int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, c
     return 0;
 }
 
+// The batched form: n requests (request i: StridedBlock i, extent, object count, origin in the one
+// typed buffer) sharing the packed buffer from `position` on.  Plans every request, groups the
+// launches into batches exactly as the library does, and runs batch_thread for every workgroup
+// and thread.  result[3] = number of batched launches, result[4] = launches left single.
+int emul_transfer_batch(int unpack, int n, const int* ndims, const int64_t* starts, const int64_t* counts,
+                        const int64_t* strides, const int64_t* extents, const int64_t* objects,
+                        const int64_t* origins, const int64_t* sizes, char* typed_buf, int64_t typed_len,
+                        char* packed_buf, int64_t packed_len, int64_t position, uint8_t* write_count,
+                        int64_t* result) {
+    std::vector<tp::Launch> launches;
+    int64_t pos = position;
+    for (int i = 0; i < n; ++i) {
+        tp::PlanInput in;
+        in.block.ndims = ndims[i];
+        in.block.start = starts[i];
+        for (int d = 0; d < ndims[i]; ++d) {
+            in.block.counts[d] = counts[i * tp::kMaxDims + d];
+            in.block.strides[d] = strides[i * tp::kMaxDims + d];
+        }
+        in.extent = extents[i];
+        in.count = objects[i];
+        in.typed = typed_buf + origins[i];
+        in.packed = packed_buf + pos;
+        std::vector<tp::Launch> mine;
+        const int rc = tp::plan_launches(in, &mine);
+        if (rc != tp::kSuccess) return rc;
+        launches.insert(launches.end(), mine.begin(), mine.end());
+        pos += objects[i] * sizes[i];
+    }
+    std::vector<tp::BatchParams> batches;
+    std::vector<tp::Launch> singles;
+    tp::make_batches(launches, &batches, &singles);
+    Checks c{typed_buf, typed_buf + typed_len, packed_buf, packed_buf + packed_len, write_count,
+             unpack ? typed_buf : packed_buf};
+    for (const tp::BatchParams& b : batches)
+        for (uint32_t blk = 0; blk < b.nblocks; ++blk)
+            for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t) {
+                if (unpack) tp::batch_thread<true>(b, blk, t, HostMem{&c});
+                else tp::batch_thread<false>(b, blk, t, HostMem{&c});
+            }
+    for (const tp::Launch& l : singles) {
+        const tp::KParams p = tp::kernel_params(l);
+        bool found;
+        if (unpack) {
+            RunLaunch<true> run{&p, l.nblocks, HostMem{&c}};
+            found = tp::dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, run);
+        } else {
+            RunLaunch<false> run{&p, l.nblocks, HostMem{&c}};
+            found = tp::dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, run);
+        }
+        if (!found) return 100;
+    }
+    result[0] = c.oob;
+    result[1] = c.misaligned;
+    result[2] = c.rewritten;
+    result[3] = static_cast<int64_t>(batches.size());
+    result[4] = static_cast<int64_t>(singles.size());
+    return 0;
+}
+
 }  // extern "C"

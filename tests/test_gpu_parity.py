@@ -374,3 +374,110 @@ def test_pinned_host_packed_side(dev):
 def test_counter_fill_matches_on_device(dev):
     a = W.fills.counter_bytes_torch(77, 100003, dev, chunk_words=4099).cpu().numpy()
     assert np.array_equal(a, W.fills.counter_bytes_numpy(77, 0, 100003))
+
+
+# ------------------------------------------------------------------ batched calls
+def test_batch_halo_equals_separate_calls(dev):
+    # all 26 regions in one tp_pack_batch / tp_unpack_batch, against the oracle and the per-call path
+    c = W.configs.cfg3()
+    grid_h = W.random_grid_f64(c["seed"] + 100, c["grid_shape"])
+    raw_h = grid_h.reshape(-1).view(np.uint8)
+    grid = to_dev(raw_h, dev)
+    send = [tp.type_from_recipe(r) for r in c["send"]]
+    ghost = [tp.type_from_recipe(r) for r in c["ghost_for_send"]]
+    total = sum(tp.type_size(h) for h in send)
+    packed = torch.zeros(total + 8, dtype=torch.uint8, device=dev)
+    say("batch halo pack")
+    b = tp.Batch([grid] * 26, [1] * 26, send)
+    assert tp.pack_batch(b, packed, total + 8, 8) == total + 8
+    plan = tp.last_plan()
+    assert plan.count("batch") == 1 and "tile" not in plan, plan
+    expect = np.zeros(total + 8, np.uint8)
+    pos = 8
+    for r in c["send"]:
+        pos = cc.pack(raw_h, 0, 1, r, expect, pos)
+    assert np.array_equal(packed.cpu().numpy(), expect)
+    say("batch halo unpack")
+    g = tp.Batch([grid] * 26, [1] * 26, ghost)
+    assert tp.unpack_batch(packed, total + 8, 8, g) == total + 8
+    want = raw_h.copy()
+    pos = 8
+    for r in c["ghost_for_send"]:
+        pos = cc.unpack(expect, pos, want, 0, 1, r)
+    assert np.array_equal(grid.cpu().numpy(), want)
+
+
+def test_batch_mixed_types_and_fallback(dev):
+    # 70 random types (some with too many dimensions for a batch descriptor) in one call
+    rng = random.Random(501)
+    reqs = []
+    typed_len = 0
+    while len(reqs) < 70:
+        t = W.random_recipe(rng, rng.randint(1, 4))
+        if py.size(t) > 4096:
+            continue
+        count = rng.randint(1, 3)
+        if py.has_overlap(t, count):
+            continue
+        d, n = cc.blocks(t, count)
+        origin = typed_len + rng.choice((0, 1, 2, 4, 8, 16))
+        typed_len = origin + int((d + n).max()) + 16
+        reqs.append((t, count, origin))
+    deep = hvector(2, 1, 100000, hvector(3, 1, 30000, hvector(2, 1, 14000, vector(3, 2, 100, hvector(2, 1, 40, named("INT16"))))))
+    assert not py.has_overlap(deep, 2)
+    reqs.insert(30, (deep, 2, typed_len))
+    typed_len += 2 * cc.extent(deep) + 16
+    typed_h = W.random_bytes(6, typed_len)
+    typed = to_dev(typed_h, dev)
+    handles = [tp.type_from_recipe(t) for t, _, _ in reqs]
+    total = sum(tp.type_size(h) * c for h, (_, c, _) in zip(handles, reqs))
+    packed = torch.full((total + 5,), 0xEE, dtype=torch.uint8, device=dev)
+    say("batch mixed pack")
+    b = tp.Batch([typed.data_ptr() + o for _, _, o in reqs], [c for _, c, _ in reqs], handles)
+    assert tp.pack_batch(b, packed, total + 5, 5) == total + 5
+    plan = tp.last_plan()
+    assert plan.count("batch") == 2 and plan.count("tile") >= 1, plan
+    expect = np.full(total + 5, 0xEE, np.uint8)
+    pos = 5
+    for t, c, o in reqs:
+        pos = cc.pack(typed_h, o, c, t, expect, pos)
+    assert np.array_equal(packed.cpu().numpy(), expect)
+    say("batch mixed unpack")
+    back = torch.full((typed_len,), 0xA5, dtype=torch.uint8, device=dev)
+    bb = tp.Batch([back.data_ptr() + o for _, _, o in reqs], [c for _, c, _ in reqs], handles)
+    assert tp.unpack_batch(packed, total + 5, 5, bb) == total + 5
+    want = np.full(typed_len, 0xA5, np.uint8)
+    pos = 5
+    for t, c, o in reqs:
+        pos = cc.unpack(expect, pos, want, o, c, t)
+    assert np.array_equal(back.cpu().numpy(), want)
+    # an invalid request anywhere: nothing is written, the position does not move
+    packed.fill_(0x11)
+    bad = tp.Batch([typed.data_ptr()] * 3, [1, 1, 1], [handles[0], 999999, handles[1]])
+    with pytest.raises(tp.TpError) as e:
+        tp.pack_batch(bad, packed, total + 5, 0)
+    assert e.value.code == tp.TP_ERR_TYPE
+    assert (packed.cpu().numpy() == 0x11).all()
+
+
+def test_batch_many_objects_of_one_type(dev):
+    # 300 separately addressed objects of the nested 4-level type: 8 batched launches instead of 300
+    c = W.configs.cfg5()
+    r = c["recipe"]
+    h = tp.type_from_recipe(r)
+    ex, size, nobj = tp.type_get_extent(h)[1], tp.type_size(h), 300
+    src = W.fills.counter_bytes_torch(c["seed"] + 7, nobj * ex, dev)
+    src_h = src.cpu().numpy()
+    out = torch.zeros(nobj * size, dtype=torch.uint8, device=dev)
+    order = list(range(nobj))
+    random.Random(3).shuffle(order)
+    say("batch 300 objects")
+    b = tp.Batch([src.data_ptr() + i * ex for i in order], [1] * nobj, [h] * nobj)
+    assert tp.pack_batch_async(b, out, nobj * size, 0) == nobj * size
+    torch.cuda.synchronize()
+    assert tp.last_plan().count("batch") == 8
+    expect = np.zeros(nobj * size, np.uint8)
+    pos = 0
+    for i in order:
+        pos = cc.pack(src_h, i * ex, 1, r, expect, pos)
+    assert np.array_equal(out.cpu().numpy(), expect)

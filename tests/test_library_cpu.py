@@ -320,3 +320,71 @@ def test_emulated_objects_that_abut_are_merged():
     assert "rows=1 " in _emulate_roundtrip(contiguous(64, BYTE), 5)["plan"]
     sub = subarray((8, 64), (8, 16), (0, 0), "C", BYTE)   # extent 512 = 8 rows of pitch 64
     assert "rows=40 nrd=1" in _emulate_roundtrip(sub, 5)["plan"]
+
+
+def test_emulated_batch_of_different_types():
+    # 71 requests of assorted types into one packed stream: batched launches of up to 40 requests,
+    # plus the requests with too many row dimensions for a batch descriptor, which stay single launches
+    rng = random.Random(77)
+    types = _random_types(305, 70, allow_negative=False)
+    types.insert(20, hvector(2, 1, 9000, hvector(3, 1, 1500, hvector(2, 1, 700, vector(3, 2, 100, hvector(2, 1, 40, INT16))))))
+    reqs, recipes = [], []
+    typed_len = 0
+    for t in types:
+        h = tp.type_from_recipe(t)
+        count = rng.randint(1, 2)
+        disps = py.byte_displacements(t, count)
+        span = max(disps) + 1
+        origin = typed_len + rng.choice((0, 1, 2, 4, 8, 16))
+        typed_len = origin + span + 16
+        reqs.append({"block": tp.type_get_strided_block(h), "extent": tp.type_get_extent(h)[1], "count": count,
+                     "origin": origin, "size": tp.type_size(h)})
+        recipes.append((t, count, origin))
+    total = sum(r["size"] * r["count"] for r in reqs)
+    typed = W.random_bytes(5, typed_len)
+    packed = np.full(total + 3, 0xEE, dtype=np.uint8)
+    res = host_emul.transfer_batch(False, reqs, typed, packed, 3)
+    assert (res["rc"], res["oob"], res["misaligned"], res["rewritten"]) == (0, 0, 0, 0), res
+    assert res["batches"] == 2 and 1 <= res["singles"] <= 30 and res["singles"] + 40 < len(types)
+    expect = np.full(total + 3, 0xEE, dtype=np.uint8)
+    pos = 3
+    for t, count, origin in recipes:
+        pos = cc.pack(typed, origin, count, t, expect, pos)
+    assert pos == total + 3 and np.array_equal(packed, expect)
+    assert (res["write_count"][3:] == 1).all()
+    back = np.full(typed_len, 0xA5, dtype=np.uint8)
+    res = host_emul.transfer_batch(True, reqs, back, packed, 3)
+    assert (res["rc"], res["oob"], res["misaligned"]) == (0, 0, 0), res
+    if not any(py.has_overlap(t, count) for t, count, _ in recipes):
+        assert res["rewritten"] == 0
+    want = np.full(typed_len, 0xA5, dtype=np.uint8)
+    pos = 3
+    for t, count, origin in recipes:
+        if not py.has_overlap(t, count):
+            pos = cc.unpack(expect, pos, want, origin, count, t)
+        else:
+            pos += py.size(t) * count
+    ok = np.ones(typed_len, dtype=bool)
+    for t, count, origin in recipes:
+        if py.has_overlap(t, count):
+            ok[np.asarray(py.byte_displacements(t, count)) + origin] = False
+    assert np.array_equal(back[ok], want[ok])
+
+
+def test_batch_error_leaves_position_unchanged():
+    L = tp.lib()
+    t = tp.type_from_recipe(vector(3, 2, 4, BYTE))
+    fake = 4096
+    ptrs = (ctypes.c_void_p * 2)(fake, fake)
+    cnts = (ctypes.c_int * 2)(1, 1)
+    pos = ctypes.c_int64(2)
+    bad = (ctypes.c_int32 * 2)(t, 999999)
+    assert L.tp_pack_batch(2, ptrs, cnts, bad, fake, 100, ctypes.byref(pos), None) == tp.TP_ERR_TYPE
+    good = (ctypes.c_int32 * 2)(t, t)
+    assert L.tp_pack_batch(2, ptrs, cnts, good, fake, 13, ctypes.byref(pos), None) == tp.TP_ERR_TRUNCATE  # 2+6+6 > 13
+    neg = (ctypes.c_int * 2)(1, -1)
+    assert L.tp_unpack_batch(2, fake, 100, ctypes.byref(pos), ptrs, neg, good, None) == tp.TP_ERR_COUNT
+    assert L.tp_pack_batch(-1, ptrs, cnts, good, fake, 100, ctypes.byref(pos), None) == tp.TP_ERR_ARG
+    assert L.tp_pack_batch(2, None, cnts, good, fake, 100, ctypes.byref(pos), None) == tp.TP_ERR_ARG
+    assert L.tp_pack_batch(0, None, None, None, None, 0, ctypes.byref(pos), None) == tp.TP_SUCCESS
+    assert pos.value == 2
