@@ -35,7 +35,20 @@ def build(verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
+    build_commit_timing()
     return LIB_PATH
+
+
+TIMING_EXE = os.path.join(PKG_DIR, "commit_timing")
+
+
+def build_commit_timing() -> str:
+    """The plain-C commit-time microbenchmark, linked against the library just built."""
+    subprocess.check_call([
+        "gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-I", INCLUDE, os.path.join(CSRC, "commit_timing.c"),
+        "-L", PKG_DIR, "-ltp_pack", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath-link," + "/opt/rocm/lib", "-o", TIMING_EXE,
+    ])
+    return TIMING_EXE
 
 
 if __name__ == "__main__":
