@@ -182,9 +182,18 @@ def main():
         "sector_bound_frac_g128": dominant["sector_bound_frac_g128"],
     }
     measured = MEASURED_TRAFFIC.get((dominant["op"], dominant["a"][0]))
-    if measured and args.packed_bytes == PACKED_BYTES and not args.override:
+    use_traffic = args.packed_bytes == PACKED_BYTES and not args.override
+    if measured and use_traffic:
         roofline["traffic"] = sum(measured)
         roofline["traffic_fetch_write"] = list(measured)
+        roofline["traffic_rate_gbs"] = round(sum(measured) / dominant["avg_us"] / 1e3, 1)
+    if use_traffic:
+        for k in kernels:   # HBM bytes actually moved per second, next to the algorithmic rate
+            m = MEASURED_TRAFFIC.get((k["op"], k["a"][0]))
+            if m:
+                k["hbm_traffic_bytes"] = sum(m)
+                k["hbm_traffic_gbs"] = round(sum(m) / k["avg_us"] / 1e3, 1)
+                k["hbm_traffic_frac_of_peak"] = round(sum(m) / k["avg_us"] / 1e3 / HBM_PEAK_GBS, 4)
 
     out = {
         "metric": "pack/unpack GB/s (read+write)", "value": round(value, 2), "unit": "GB/s",
@@ -390,6 +399,17 @@ def other_workloads(W, tp, torch, arena, dev, stream):
                                "batched_one_launch_call_and_sync_us": round(t_b_wall, 1),
                                "gbs_batched_event": round(2 * total / t_b_ev / 1e3, 1),
                                "gbs_batched_call_and_sync": round(2 * total / t_b_wall / 1e3, 1)})
+    # the 26 pack calls captured once in a HIP graph (what an iterative application would replay)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        pos = 0
+        for h in send:
+            pos = tp.pack_async(grid_at(0), 1, h, bufs[0], total, pos, torch.cuda.current_stream())
+    t_graph = median_wall_us(lambda k: (graph.replay(), torch.cuda.synchronize()), 12)
+    halo_res["pack"]["26_calls_hip_graph_replay_and_sync_us"] = round(t_graph, 1)
+    del graph
     # per class: one x-face (24-byte runs), one y-face, one z-face (4048-byte runs)
     dirs = c3["directions"]
     for label, d in (("x_face", (0, 0, -1)), ("y_face", (0, -1, 0)), ("z_face", (-1, 0, 0))):

@@ -481,3 +481,36 @@ def test_batch_many_objects_of_one_type(dev):
     for i in order:
         pos = cc.pack(src_h, i * ex, 1, r, expect, pos)
     assert np.array_equal(out.cpu().numpy(), expect)
+
+
+def test_async_calls_replay_from_a_hip_graph(dev):
+    # the enqueue-only entry points allocate nothing and record no memset, so a stream capture of
+    # them replays correctly: capture the 26 halo packs once, replay after changing the grid
+    c = W.configs.cfg3(32, 3)
+    n = 32
+    send = [tp.type_from_recipe(r) for r in c["send"]]
+    total = sum(tp.type_size(h) for h in send)
+    grid = torch.zeros(n * n * n * 8, dtype=torch.uint8, device=dev)
+    packed = torch.zeros(total, dtype=torch.uint8, device=dev)
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    say("capture 26 pack_async calls")
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=side):
+        pos = 0
+        for h in send:
+            pos = tp.pack_async(grid, 1, h, packed, total, pos, torch.cuda.current_stream())
+    assert pos == total
+    for rep in range(4):
+        say("replay", rep)
+        grid_h = W.random_grid_f64(700 + rep, (n, n, n)).reshape(-1).view(np.uint8)
+        grid.copy_(torch.from_numpy(grid_h))       # eager work between replays
+        packed.fill_(0x5A)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        expect = np.zeros(total, np.uint8)
+        p = 0
+        for r in c["send"]:
+            p = cc.pack(grid_h, 0, 1, r, expect, p)
+        assert np.array_equal(packed.cpu().numpy(), expect)
