@@ -300,11 +300,42 @@ def extras(W, tp, torch, np, dev, stream):
     # commit time per type: the plain-C program timing create and commit through the C ABI,
     # trimean of 30000 cycles per type (the statistic of the paper's Sec. 6.1)
     import subprocess
+    import tempfile
+
+    # measured performance model (paper Sec. 4 / 6.3): measure the system, keep the table, and ask it
+    # which way packed data should reach the host for a few shapes
+    from oracle import model as om  # only to parse the saved table for the report
+    model_path = os.path.join(tempfile.mkdtemp(prefix="tp_model_"), "model.txt")
+    t0 = time.perf_counter()
+    tp.model_measure(stream)
+    measure_s = time.perf_counter() - t0
+    tp.model_save(model_path)
+    table = om.parse(open(model_path).read())
+    model = {"measure_seconds": round(measure_s, 2), "sizes": table["sizes"].tolist(), "blocks": table["blocks"].tolist()}
+    for name in om.PRIMITIVES:
+        model[name + "_us"] = np.round(table[name] * 1e6, 2).tolist()
+    picks = []
+    for label, recipe, count in (("64 KiB in 8-byte runs", W.vector(8192, 8, 512, W.BYTE), 1),
+                                 ("4 MiB in 64-byte runs", W.vector(65536, 64, 512, W.BYTE), 1),
+                                 ("4 MiB in 4 KiB runs", W.vector(1024, 4096, 8192, W.BYTE), 1),
+                                 ("64 MiB in 4 KiB runs", W.vector(16384, 4096, 8192, W.BYTE), 1)):
+        hh = tp.type_from_recipe(recipe)
+        q = tp.model_query(hh, count)
+        picks.append({"object": label, "host_pack_us": round(q["host_pack"] * 1e6, 1),
+                      "gpu_pack_plus_d2h_us": round((q["gpu_pack"] + q["d2h"]) * 1e6, 1),
+                      "to_host": "staged" if q["gpu_pack"] + q["d2h"] < q["host_pack"] else "one-shot"})
+    model["to_host_choice"] = picks
+    res["model"] = model
+
     exe = os.path.join(ROOT, "paper_2012_14363_amd", "commit_timing")
     if os.path.exists(exe):
         try:
-            rows = json.loads(subprocess.run([exe, "30000"], capture_output=True, text=True, timeout=120,
+            rows = json.loads(subprocess.run([exe, "30000", model_path], capture_output=True, text=True, timeout=120,
                                              check=True).stdout)
+            select = [r for r in rows if r["type"].startswith("tp_model_select")]
+            rows = [r for r in rows if not r["type"].startswith("tp_model_select")]
+            if select:
+                res["model"]["select_ns_per_query_memoised"] = select[0]["ns_per_query"]
             res["canonicalize_us_per_type"] = [
                 {"type": r["type"], "shape": r["shape"], "canonical_dims": r["canonical_dims"],
                  "create_us": round(r["create_trimean_ns"] / 1e3, 3),

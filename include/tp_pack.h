@@ -153,6 +153,52 @@ int tp_pack_batch_async(int n, const void *const inbufs[], const int incounts[],
 int tp_unpack_batch_async(int n, const void *inbuf, int64_t insize, int64_t *position, void *const outbufs[],
                           const int outcounts[], const tp_type types[], void *hip_stream);
 
+/* ---- measured performance model and host delivery (Sec. 4, Eq. 1-3; Sec. 6.3) -------------------
+ * When packed data has to reach host memory (to be handed to a transport that cannot read device
+ * memory), it can be packed straight into pinned host memory ("one-shot", zero-copy) or packed into
+ * device memory and copied ("staged"); Sec. 4 also has the "device" method, where the packed
+ * device buffer itself is handed to a GPU-aware transport.  Which is fastest depends on object size
+ * and contiguous block length, so the paper measures the system once and interpolates at run time.
+ *
+ * tp_model_measure: times six primitives on the current device - pack/unpack with the contiguous
+ *     side in device memory and in pinned host memory, and plain D2H / H2D copies - each as
+ *     launch + execute + synchronize (the paper's timed region), on a sparse grid of object sizes
+ *     (64 B .. 4 MiB) x contiguous block lengths (1 B .. 4 KiB) of 2D objects with 512-byte pitch,
+ *     and installs the table as the process-wide model.  It is the "system measurement" step, not
+ *     part of the pack path: it allocates and frees its own device and pinned buffers (~2 GiB).
+ * tp_model_save / tp_model_load: the table as a small text file.
+ * tp_model_query: interpolated times (seconds) for `count` objects of committed type t: bilinear in
+ *     (log2 bytes, log2 block) where bytes = count*size and block = the canonical contiguous run
+ *     (the whole message for a dense type); block clamped to the measured range, bytes clamped below
+ *     it and scaled proportionally above it.  Results are memoised.  TP_ERR_ARG if no model is loaded.
+ * tp_model_select: Eq. 1-3.  t_cpu_cpu and t_gpu_gpu are the transport terms, which need a second
+ *     rank to measure and are therefore inputs (seconds; 0 if unknown).  *method receives the
+ *     fastest of TP_METHOD_DEVICE / ONESHOT / STAGED; times (may be NULL) the three totals.
+ * tp_pack_host: tp_pack whose outbuf is pinned host memory, by the method asked for:
+ *     TP_METHOD_ONESHOT, TP_METHOD_STAGED (needs `staging`, device memory of at least incount*size
+ *     bytes, caller-owned), or TP_METHOD_AUTO (staged if the model predicts gpu_pack + d2h <
+ *     host_pack and staging is large enough, else one-shot).  Synchronizes.  *method_used (may be
+ *     NULL) reports the choice.  tp_unpack_host is the mirror (host inbuf -> device typed buffer).
+ */
+typedef struct tp_model_times {
+    double gpu_pack, gpu_unpack, host_pack, host_unpack, d2h, h2d;
+} tp_model_times;
+
+#define TP_METHOD_AUTO (-1)
+#define TP_METHOD_DEVICE 0
+#define TP_METHOD_ONESHOT 1
+#define TP_METHOD_STAGED 2
+
+int tp_model_measure(void *hip_stream);
+int tp_model_save(const char *path);
+int tp_model_load(const char *path);
+int tp_model_query(tp_type t, int count, tp_model_times *out);
+int tp_model_select(tp_type t, int count, double t_cpu_cpu, double t_gpu_gpu, int *method, double times[3]);
+int tp_pack_host(const void *inbuf, int incount, tp_type t, void *host_outbuf, int64_t outsize, int64_t *position,
+                 void *staging, int64_t staging_size, int method, void *hip_stream, int *method_used);
+int tp_unpack_host(const void *host_inbuf, int64_t insize, int64_t *position, void *outbuf, int outcount, tp_type t,
+                   void *staging, int64_t staging_size, int method, void *hip_stream, int *method_used);
+
 /* ---- introspection for tests and ablations ------------------------------------------------------
  * tp_type_get_strided_block: the canonical form of a committed type (Sec. 3.3): *ndims dimensions,
  * counts[0] contiguous bytes with strides[0] == 1, dimension d+1 repeats dimension d counts[d+1]

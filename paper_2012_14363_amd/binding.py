@@ -31,8 +31,21 @@ EXPORTS = (
     "tp_type_commit", "tp_type_free", "tp_type_size", "tp_type_get_extent", "tp_pack_size",
     "tp_pack", "tp_unpack", "tp_pack_async", "tp_unpack_async",
     "tp_pack_batch", "tp_unpack_batch", "tp_pack_batch_async", "tp_unpack_batch_async",
+    "tp_model_measure", "tp_model_save", "tp_model_load", "tp_model_query", "tp_model_select",
+    "tp_pack_host", "tp_unpack_host",
     "tp_type_get_strided_block", "tp_set_override", "tp_last_plan", "tp_error_string",
 )
+
+
+TP_METHOD_AUTO, TP_METHOD_DEVICE, TP_METHOD_ONESHOT, TP_METHOD_STAGED = -1, 0, 1, 2
+
+
+class ModelTimes(ctypes.Structure):
+    """tp_model_times: seconds per operation."""
+    _fields_ = [(n, ctypes.c_double) for n in ("gpu_pack", "gpu_unpack", "host_pack", "host_unpack", "d2h", "h2d")]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
 
 
 class TpError(RuntimeError):
@@ -81,6 +94,14 @@ def lib() -> ctypes.CDLL:
             "tp_unpack_batch": [ctypes.c_int, vp, i64, pi64, pvp, pint, pi32, vp],
             "tp_pack_batch_async": [ctypes.c_int, pvp, pint, pi32, vp, i64, pi64, vp],
             "tp_unpack_batch_async": [ctypes.c_int, vp, i64, pi64, pvp, pint, pi32, vp],
+            "tp_model_measure": [vp],
+            "tp_model_save": [ctypes.c_char_p],
+            "tp_model_load": [ctypes.c_char_p],
+            "tp_model_query": [i32, ctypes.c_int, ctypes.POINTER(ModelTimes)],
+            "tp_model_select": [i32, ctypes.c_int, ctypes.c_double, ctypes.c_double, pint,
+                                ctypes.POINTER(ctypes.c_double)],
+            "tp_pack_host": [vp, ctypes.c_int, i32, vp, i64, pi64, vp, i64, ctypes.c_int, vp, pint],
+            "tp_unpack_host": [vp, i64, pi64, vp, ctypes.c_int, i32, vp, i64, ctypes.c_int, vp, pint],
             "tp_type_get_strided_block": [i32, pint, pi64, pi64, pi64],
             "tp_set_override": [ctypes.c_char_p, ctypes.c_char_p],
         }
@@ -269,6 +290,55 @@ def unpack_batch(inbuf, insize: int, position: int, batch: Batch, stream=None) -
 
 def unpack_batch_async(inbuf, insize: int, position: int, batch: Batch, stream=None) -> int:
     return _batch("tp_unpack_batch_async", batch, inbuf, insize, position, stream)
+
+
+# ------------------------------------------------------------------ model and host delivery
+def model_measure(stream=None) -> None:
+    _check(lib().tp_model_measure(_stream(stream)), "tp_model_measure")
+
+
+def model_save(path: str) -> None:
+    _check(lib().tp_model_save(path.encode()), "tp_model_save")
+
+
+def model_load(path: str) -> None:
+    _check(lib().tp_model_load(path.encode()), "tp_model_load")
+
+
+def model_query(t: int, count: int) -> dict:
+    m = ModelTimes()
+    _check(lib().tp_model_query(t, count, ctypes.byref(m)), "tp_model_query")
+    return m.as_dict()
+
+
+def model_select(t: int, count: int, t_cpu_cpu: float = 0.0, t_gpu_gpu: float = 0.0):
+    """(method, [T_device, T_oneshot, T_staged])"""
+    method = ctypes.c_int(-9)
+    times = (ctypes.c_double * 3)()
+    _check(lib().tp_model_select(t, count, t_cpu_cpu, t_gpu_gpu, ctypes.byref(method), times), "tp_model_select")
+    return method.value, list(times)
+
+
+def pack_host(inbuf, incount, t, host_outbuf, outsize, position, staging=None, staging_size=0,
+              method=TP_METHOD_AUTO, stream=None):
+    """tp_pack_host; returns (new position, method used)."""
+    pos, used = ctypes.c_int64(position), ctypes.c_int(-9)
+    rc = lib().tp_pack_host(_ptr(inbuf), incount, t, _ptr(host_outbuf), outsize, ctypes.byref(pos),
+                            _ptr(staging) if staging is not None else None, staging_size, method, _stream(stream),
+                            ctypes.byref(used))
+    _check(rc, "tp_pack_host")
+    return pos.value, used.value
+
+
+def unpack_host(host_inbuf, insize, position, outbuf, outcount, t, staging=None, staging_size=0,
+                method=TP_METHOD_AUTO, stream=None):
+    """tp_unpack_host; returns (new position, method used)."""
+    pos, used = ctypes.c_int64(position), ctypes.c_int(-9)
+    rc = lib().tp_unpack_host(_ptr(host_inbuf), insize, ctypes.byref(pos), _ptr(outbuf), outcount, t,
+                              _ptr(staging) if staging is not None else None, staging_size, method, _stream(stream),
+                              ctypes.byref(used))
+    _check(rc, "tp_unpack_host")
+    return pos.value, used.value
 
 
 # ------------------------------------------------------------------ recipes -> handles

@@ -10,7 +10,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.path.join(PKG_DIR, "libtp_pack.so")
 
-SOURCES = ["api.cpp", "type_tree.cpp", "canon.cpp", "plan.cpp", "kernels.hip"]
+SOURCES = ["api.cpp", "model_api.cpp", "model.cpp", "type_tree.cpp", "canon.cpp", "plan.cpp", "kernels.hip"]
 
 
 def hipcc() -> str:

@@ -125,9 +125,12 @@ int check_request(const void* typed_buf, int64_t count, tp_type t, const void* p
 // Resolves the buffers of a checked request and appends its planned launches to `launches`.
 int plan_request(bool unpack, const TypeNode& node, const void* typed_buf, int64_t count, PackedSide* packed,
                  int64_t position, std::vector<Launch>* launches) {
-    const char* typed_view = nullptr;
-    int rc = resolve_pointer(typed_buf, false, &typed_view);
+    // Query the first selected byte, not the origin: MPI lets the origin lie outside the
+    // allocation (negative strides, lower bounds above zero); the data never does.
+    const char* first_byte = nullptr;
+    int rc = resolve_pointer(static_cast<const char*>(typed_buf) + node.block.start, false, &first_byte);
     if (rc != kSuccess) return rc;
+    const char* typed_view = first_byte - node.block.start;
     rc = packed->resolve();
     if (rc != kSuccess) return rc;
     PlanInput in;

@@ -8,8 +8,12 @@
  * parameter sets exist only in its figure; the shapes here stand in (the same ones
  * workloads/configs.py lists), plus the five benchmark datatypes.
  *
+ * With a model file (written by tp_model_save) it also times the memoised
+ * performance-model query, tp_model_select, the overhead the paper reports in
+ * Sec. 6.3 for its own model.
+ *
  * Plain C on purpose: it also proves include/tp_pack.h is usable from C.
- * Output: one JSON array on stdout.  Usage: commit_timing [iterations]
+ * Output: one JSON array on stdout.  Usage: commit_timing [iterations [model_file]]
  */
 #define _POSIX_C_SOURCE 199309L
 #include <stdio.h>
@@ -176,6 +180,24 @@ int main(int argc, char **argv) {
                    trimean(t_create, iters), trimean(t_commit, iters));
             first = 0;
         }
+    }
+    if (argc > 2) {
+        check(tp_model_load(argv[2]));
+        tp_type t = b_cfg_halo_face(&shapes[0]);
+        check(tp_type_commit(&t));
+        const int n = 1000000;
+        int method = 0, sum = 0;
+        double times[3];
+        check(tp_model_select(t, 1, 5e-6, 20e-6, &method, times)); /* first call interpolates, the rest hit the memo */
+        double t0 = now_ns();
+        for (int i = 0; i < n; ++i) {
+            check(tp_model_select(t, 1, 5e-6, 20e-6, &method, times));
+            sum += method;
+        }
+        double per = (now_ns() - t0) / n;
+        printf(", {\"type\": \"tp_model_select (memoised)\", \"iterations\": %d, \"ns_per_query\": %.1f, \"method\": %d}",
+               n, per, sum / n);
+        tp_type_free(&t);
     }
     printf("]\n");
     free(t_create);

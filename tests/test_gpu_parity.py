@@ -142,6 +142,14 @@ def test_empty_and_degenerate(dev):
     roundtrip(BYTE, 1, dev)
     roundtrip(DOUBLE, 7, dev, typed_shift=8)
     roundtrip(contiguous(1 << 20, BYTE), 1, dev, typed_shift=1, packed_shift=3)   # unaligned plain copy
+    # the origin handed to pack may lie outside the allocation as long as the selected bytes do not
+    say("origin before the allocation")
+    sub = tp.type_from_recipe(subarray((8, 512), (2, 16), (4, 0), "C", BYTE))   # first byte at +2048
+    data_h = W.random_bytes(8, 1024)
+    data = to_dev(data_h, dev)
+    out2 = torch.zeros(32, dtype=torch.uint8, device=dev)
+    assert tp.pack(data.data_ptr() - 2048, 1, sub, out2, 32, 0) == 32
+    assert np.array_equal(out2.cpu().numpy(), np.concatenate([data_h[0:16], data_h[512:528]]))
 
 
 def test_pageable_host_memory_is_rejected(dev):
@@ -514,3 +522,58 @@ def test_async_calls_replay_from_a_hip_graph(dev):
         for r in c["send"]:
             p = cc.pack(grid_h, 0, 1, r, expect, p)
         assert np.array_equal(packed.cpu().numpy(), expect)
+
+
+# ------------------------------------------------------------------ model and host delivery
+def test_model_measure_and_host_delivery(dev, tmp_path):
+    from oracle import model as om
+    say("tp_model_measure")
+    tp.model_measure()
+    path = tmp_path / "model.txt"
+    tp.model_save(str(path))
+    table = om.parse(path.read_text())
+    for name in om.PRIMITIVES:
+        assert (table[name] > 0).all() and (table[name] < 1.0).all(), name
+    # the largest objects cost more than the smallest, and every call has a latency floor above 1 us
+    assert (table["gpu_pack"][-1] > table["gpu_pack"][0]).all() and table["gpu_pack"].min() > 1e-6
+    assert table["d2h"][-1] > table["d2h"][0]
+    # the library's interpolation of its own measured table equals the oracle's
+    t = vector(5000, 24, 512, BYTE)
+    h = tp.type_from_recipe(t)
+    size = tp.type_size(h)
+    want = om.query(table, size * 3, 24)
+    got = tp.model_query(h, 3)
+    assert all(abs(got[k] - want[k]) <= 1e-12 * want[k] for k in want)
+    m, totals = tp.model_select(h, 3)
+    assert (m, totals) == (om.select(want)[0], pytest.approx(om.select(want)[1], rel=1e-12))
+
+    ex = tp.type_get_extent(h)[1]
+    src_h = W.random_bytes(21, ex * 3)
+    src = to_dev(src_h, dev)
+    expect = np.full(size * 3 + 4, 0xEE, np.uint8)
+    cc.pack(src_h, 0, 3, t, expect, 4)
+    staging = torch.zeros(size * 3, dtype=torch.uint8, device=dev)
+    for method in (tp.TP_METHOD_ONESHOT, tp.TP_METHOD_STAGED, tp.TP_METHOD_AUTO):
+        say("pack_host method", method)
+        host = torch.full((size * 3 + 4,), 0xEE, dtype=torch.uint8).pin_memory()
+        pos, used = tp.pack_host(src, 3, h, host, size * 3 + 4, 4, staging, size * 3, method)
+        assert pos == size * 3 + 4 and used in (tp.TP_METHOD_ONESHOT, tp.TP_METHOD_STAGED)
+        if method != tp.TP_METHOD_AUTO:
+            assert used == method
+        else:
+            assert used == (tp.TP_METHOD_STAGED if want["gpu_pack"] + want["d2h"] < want["host_pack"]
+                            else tp.TP_METHOD_ONESHOT)
+        assert np.array_equal(host.numpy(), expect)
+        back = torch.full((ex * 3,), 0xA5, dtype=torch.uint8, device=dev)
+        pos, used = tp.unpack_host(host, size * 3 + 4, 4, back, 3, h, staging, size * 3, method)
+        assert pos == size * 3 + 4
+        wantb = np.full(ex * 3, 0xA5, np.uint8)
+        cc.unpack(expect, 4, wantb, 0, 3, t)
+        assert np.array_equal(back.cpu().numpy(), wantb)
+    # staged without a large enough staging buffer is an argument error; auto falls back to one-shot
+    host = torch.zeros(size * 3, dtype=torch.uint8).pin_memory()
+    with pytest.raises(tp.TpError) as e:
+        tp.pack_host(src, 3, h, host, size * 3, 0, staging, 10, tp.TP_METHOD_STAGED)
+    assert e.value.code == tp.TP_ERR_ARG
+    assert tp.pack_host(src, 3, h, host, size * 3, 0, None, 0, tp.TP_METHOD_AUTO) == (size * 3, tp.TP_METHOD_ONESHOT)
+    assert np.array_equal(host.numpy(), expect[4:])
