@@ -27,11 +27,20 @@ std::atomic<bool> g_check_buffers{true};
 std::atomic<int64_t> g_max_rows_per_launch{int64_t{1} << 30};
 std::atomic<int64_t> g_max_words_per_run{int64_t{1} << 30};
 
-thread_local std::string t_last_plan;
+// What the calling thread's last pack/unpack enqueued; formatted only when tp_last_plan() asks.
+struct LastPlan {
+    std::vector<BatchParams> batches;
+    std::vector<Launch> launches;
+    std::string text;
+    void clear() {
+        batches.clear();
+        launches.clear();
+    }
+};
+thread_local LastPlan t_last_plan;
 thread_local std::string t_last_hip_error;
 
-int register_type(int status, TypePtr node, tp_type* newtype) {
-    if (status != kSuccess) return status;
+int register_type(TypePtr node, tp_type* newtype) {
     const int32_t h = HandleTable::instance().insert(std::move(node));
     if (h < 0) return kErrRange;
     *newtype = h;
@@ -123,7 +132,7 @@ int check_request(const void* typed_buf, int64_t count, tp_type t, const void* p
 }
 
 // Resolves the buffers of a checked request and appends its planned launches to `launches`.
-int plan_request(bool unpack, const TypeNode& node, const void* typed_buf, int64_t count, PackedSide* packed,
+int plan_request(const TypeNode& node, const void* typed_buf, int64_t count, PackedSide* packed,
                  int64_t position, std::vector<Launch>* launches) {
     // Query the first selected byte, not the origin: MPI lets the origin lie outside the
     // allocation (negative strides, lower bounds above zero); the data never does.
@@ -141,7 +150,6 @@ int plan_request(bool unpack, const TypeNode& node, const void* typed_buf, int64
     in.packed = const_cast<char*>(packed->view) + position;
     in.max_word_log2 = g_max_word_log2.load(std::memory_order_relaxed);
     in.nt = g_nt.load(std::memory_order_relaxed);
-    in.unpack = unpack;
     in.max_rows_per_launch = g_max_rows_per_launch.load(std::memory_order_relaxed);
     in.max_words_per_run = g_max_words_per_run.load(std::memory_order_relaxed);
     std::vector<Launch> mine;
@@ -174,11 +182,11 @@ int transfer(bool unpack, const void* typed_buf, int64_t count, tp_type t, const
     if (rc != kSuccess) return rc;
     std::vector<Launch> launches;
     if (bytes > 0) {
-        rc = plan_request(unpack, *node, typed_buf, count, &packed, *position, &launches);
+        rc = plan_request(*node, typed_buf, count, &packed, *position, &launches);
         if (rc != kSuccess) return rc;
     }
     const int64_t pos = *position + bytes;
-    t_last_plan = describe(launches);
+    t_last_plan.launches = launches;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     for (const Launch& l : launches) {
         const hipError_t e = enqueue(l, unpack, stream);
@@ -219,13 +227,14 @@ int transfer_batch(bool unpack, int n, const void* const* typed_bufs, const int*
     std::vector<Launch> launches;
     for (int i = 0; i < n; ++i) {
         if (sizes[i] == 0) continue;
-        const int rc = plan_request(unpack, *nodes[i], typed_bufs[i], counts[i], &packed, offsets[i], &launches);
+        const int rc = plan_request(*nodes[i], typed_bufs[i], counts[i], &packed, offsets[i], &launches);
         if (rc != kSuccess) return rc;
     }
     std::vector<BatchParams> batches;
     std::vector<Launch> singles;
     make_batches(launches, &batches, &singles);
-    t_last_plan = describe(batches) + describe(singles);
+    t_last_plan.batches = batches;
+    t_last_plan.launches = singles;
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
     for (const BatchParams& b : batches) {
         const hipError_t e = enqueue_batch(b, unpack, stream);
@@ -258,7 +267,9 @@ int tp_type_contiguous(int count, tp_type old, tp_type* newtype) {
     const TypePtr o = HandleTable::instance().lookup(old);
     if (!o) return kErrType;
     TypePtr n;
-    return register_type(make_contiguous(count, o, &n), n, newtype);
+    const int rc = make_contiguous(count, o, &n);
+    if (rc != kSuccess) return rc;
+    return register_type(std::move(n), newtype);
 }
 
 int tp_type_vector(int count, int blocklength, int stride, tp_type old, tp_type* newtype) {
@@ -266,7 +277,9 @@ int tp_type_vector(int count, int blocklength, int stride, tp_type old, tp_type*
     const TypePtr o = HandleTable::instance().lookup(old);
     if (!o) return kErrType;
     TypePtr n;
-    return register_type(make_vector(count, blocklength, stride, false, o, &n), n, newtype);
+    const int rc = make_vector(count, blocklength, stride, false, o, &n);
+    if (rc != kSuccess) return rc;
+    return register_type(std::move(n), newtype);
 }
 
 int tp_type_create_hvector(int count, int blocklength, int64_t stride_bytes, tp_type old, tp_type* newtype) {
@@ -274,7 +287,9 @@ int tp_type_create_hvector(int count, int blocklength, int64_t stride_bytes, tp_
     const TypePtr o = HandleTable::instance().lookup(old);
     if (!o) return kErrType;
     TypePtr n;
-    return register_type(make_vector(count, blocklength, stride_bytes, true, o, &n), n, newtype);
+    const int rc = make_vector(count, blocklength, stride_bytes, true, o, &n);
+    if (rc != kSuccess) return rc;
+    return register_type(std::move(n), newtype);
 }
 
 int tp_type_create_subarray(int ndims, const int sizes[], const int subsizes[], const int starts[], int order,
@@ -283,7 +298,9 @@ int tp_type_create_subarray(int ndims, const int sizes[], const int subsizes[], 
     const TypePtr o = HandleTable::instance().lookup(old);
     if (!o) return kErrType;
     TypePtr n;
-    return register_type(make_subarray(ndims, sizes, subsizes, starts, order, o, &n), n, newtype);
+    const int rc = make_subarray(ndims, sizes, subsizes, starts, order, o, &n);
+    if (rc != kSuccess) return rc;
+    return register_type(std::move(n), newtype);
 }
 
 int tp_type_commit(tp_type* t) {
@@ -424,7 +441,10 @@ int tp_set_override(const char* key, const char* value) {
     return kErrArg;
 }
 
-const char* tp_last_plan(void) { return t_last_plan.c_str(); }
+const char* tp_last_plan(void) {
+    t_last_plan.text = describe(t_last_plan.batches) + describe(t_last_plan.launches);
+    return t_last_plan.text.c_str();
+}
 
 const char* tp_error_string(int code) {
     switch (code) {

@@ -113,7 +113,6 @@ bool stream_elision(Chain& chain) {
 bool stream_flatten(Chain& chain) {
     bool changed = false;
     for (size_t i = chain.size(); i-- > 1;) {
-        if (i >= chain.size()) continue;
         Level& parent = chain[i - 1];
         const Level& child = chain[i];
         if (parent.dense || child.dense) continue;

@@ -52,7 +52,6 @@ struct PlanInput {
     char* packed = nullptr;        // contiguous buffer + position
     int max_word_log2 = 4;   // override: cap on the access width
     int nt = -1;             // override: streaming hints (-1 = planner's choice)
-    bool unpack = false;
     int64_t max_rows_per_launch = int64_t{1} << 30;   // tests lower these to force splitting
     int64_t max_words_per_run = int64_t{1} << 30;
 };

@@ -36,8 +36,14 @@ def _load():
         L.emul_transfer_batch.argtypes = [ctypes.c_int, ctypes.c_int, pint, p64, p64, p64, p64, p64, p64, p64, vp, i64,
                                           vp, i64, i64, vp, p64]
         L.emul_transfer_batch.restype = ctypes.c_int
+        L.emul_fastdiv_mismatches.argtypes = [ctypes.c_uint32, i64, ctypes.c_uint64]
+        L.emul_fastdiv_mismatches.restype = i64
         _lib = L
     return _lib
+
+
+def fastdiv_mismatches(small_limit, random_pairs, seed):
+    return _load().emul_fastdiv_mismatches(small_limit, random_pairs, seed)
 
 
 def transfer(unpack, block, extent, count, typed, origin, packed, position, *, max_word=16,

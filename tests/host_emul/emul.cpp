@@ -124,6 +124,35 @@ int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, c
     return 0;
 }
 
+// Multiply-shift division (fastdiv.hpp) against the hardware divide: every divisor in
+// [1, small_limit] with dividends around multiples of it and at the range ends, plus `random_pairs`
+// pseudo-random (dividend < 2^31, divisor) pairs, powers of two included.  Returns the mismatches.
+int64_t emul_fastdiv_mismatches(uint32_t small_limit, int64_t random_pairs, uint64_t seed) {
+    int64_t bad = 0;
+    auto check = [&bad](uint32_t n, const tp::FastDiv& f) {
+        n &= 0x7fffffffu;
+        if (tp::fastdiv(n, f) != n / f.divisor) ++bad;
+    };
+    for (uint32_t d = 1; d <= small_limit; ++d) {
+        const tp::FastDiv f = tp::make_fastdiv(d);
+        const uint32_t top = 0x7fffffffu / d * d;
+        for (uint32_t n : {0u, 1u, d - 1, d, d + 1, 2 * d - 1, 2 * d, top - 1, top, top + 1, 0x7fffffffu, 0x7ffffffeu})
+            check(n, f);
+    }
+    uint64_t x = seed | 1;
+    auto next = [&x]() { x ^= x << 13; x ^= x >> 7; x ^= x << 17; return x; };
+    for (int64_t k = 0; k < random_pairs; ++k) {
+        uint32_t d = static_cast<uint32_t>(next() & 0x7fffffffu) | 1u;
+        if (k % 3 == 0) d = 1u << (next() % 31);
+        if (k % 3 == 1) d = (d % 70000u) + 1u;
+        const tp::FastDiv f = tp::make_fastdiv(d);
+        check(static_cast<uint32_t>(next()), f);
+        check(0x7fffffffu, f);
+        check(0x7fffffffu / d * d, f);
+    }
+    return bad;
+}
+
 // The batched form: n requests (request i: StridedBlock i, extent, object count, origin in the one
 // typed buffer) sharing the packed buffer from `position` on.  Plans every request, groups the
 // launches into batches exactly as the library does, and runs batch_thread for every workgroup

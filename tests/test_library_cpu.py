@@ -388,3 +388,36 @@ def test_batch_error_leaves_position_unchanged():
     assert L.tp_pack_batch(2, None, cnts, good, fake, 100, ctypes.byref(pos), None) == tp.TP_ERR_ARG
     assert L.tp_pack_batch(0, None, None, None, None, 0, ctypes.byref(pos), None) == tp.TP_SUCCESS
     assert pos.value == 2
+
+
+def test_multiply_shift_division_is_exact():
+    # the kernels turn row indices into coordinates with this; checked against the hardware divide
+    assert host_emul.fastdiv_mismatches(100000, 3000000, 12345) == 0
+
+
+def test_handle_table_and_commit_are_thread_safe():
+    import threading
+
+    recipe = W.configs.cfg5()["recipe"]
+    shared = tp.type_from_recipe(recipe, commit=False)
+    errors = []
+
+    def worker(seed):
+        try:
+            rng = random.Random(seed)
+            for _ in range(300):
+                tp.type_commit(shared)                      # racing commits of one handle
+                assert tp.type_get_strided_block(shared)[1] == [4096, 8, 16, 4]
+                t = W.random_recipe(rng, rng.randint(1, 3))
+                h = tp.type_from_recipe(t)
+                assert tp.type_size(h) == cc.size(t)
+                if h >= 12:
+                    tp.type_free(h)
+        except Exception as e:  # noqa: BLE001
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(s,)) for s in range(8)]
+    [t.start() for t in threads]
+    [t.join() for t in threads]
+    assert not errors, errors[:1]
+    tp.type_free(shared)
