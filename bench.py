@@ -34,8 +34,8 @@ PACKED_BYTES = 1 << 26
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--packed-bytes", type=int, default=PACKED_BYTES, help="packed bytes per sweep point")
     ap.add_argument("--override", action="append", default=[], metavar="KEY=VALUE",
                     help="planner override passed to tp_set_override (ablations), e.g. nt=0 or word=4")
@@ -164,14 +164,21 @@ def main():
         for i, p in enumerate(points):
             ms = [all_events[k][d][i][0].elapsed_time(all_events[k][d][i][1]) for k in range(args.steps)]
             avg_us = 1e3 * sum(ms) / len(ms)
+            srt = sorted(ms)
             alg = 2 * p["packed_bytes"]
             run = int(plans[i].split("n0=")[1].split()[0]) * int(plans[i].split("W=")[1].split()[0])
             kernels.append({
                 "op": op, "a": list(p["a"]), "plan": plans[i], "avg_us": round(avg_us, 2),
+                "median_us": round(1e3 * srt[len(srt) // 2], 2), "min_us": round(1e3 * srt[0], 2),
                 "algorithmic_bytes": alg, "gbs": round(alg / avg_us / 1e3, 1),
                 "frac_of_peak": round(alg / avg_us / 1e3 / HBM_PEAK_GBS, 4),
                 "sector_bound_frac_g128": round(sector_bound_fraction(run), 4),
             })
+    # the same-size plain copy through the same kernel (the dense a0 = 512 point) is the copy ceiling
+    ceiling = {k["op"]: k["gbs"] for k in kernels if k["a"][0] == 512}
+    for k in kernels:
+        if k["op"] in ceiling:
+            k["frac_of_copy_ceiling"] = round(k["gbs"] / ceiling[k["op"]], 4)
     dominant = max(kernels, key=lambda k: k["avg_us"])
     roofline = {
         "bound": "hbm", "kernel": f"{dominant['op']} a={dominant['a']} [{dominant['plan']}]",
@@ -241,7 +248,14 @@ def cpu_baseline(W, np):
             break
     dt = time.perf_counter() - t0
     moved = reps * sum(2 * p["packed_bytes"] for p in pts) * 2
+    t0 = time.perf_counter()
+    for p, o in zip(pts, outs):
+        cc.pack(src, 0, 1, p["recipe"], o, 0, nthreads=1)
+    for p, o in zip(pts, outs):
+        cc.unpack(o, 0, src, 0, 1, p["recipe"], nthreads=1)
+    single = sum(2 * p["packed_bytes"] for p in pts) * 2 / (time.perf_counter() - t0) / 1e9
     return {"value": round(moved / dt / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
+            "single_thread_value": round(single, 3),
             "sample": f"same sweep at 8 MiB packed per point (outermost dimension / 8), {reps} passes of "
                       f"pack+unpack over all 10 points, {cores} threads over the outermost loop"}
 
@@ -282,6 +296,9 @@ def extras(W, tp, torch, np, dev, stream):
         k[0] += 1
     us = timed(own_copy, n=24)
     res["copy_ceiling_tp_1d_64MiB"] = {"us": round(us, 2), "gbs": round(2 * n / us / 1e3, 1)}
+    # the same copy without rotation: source and destination stay in the 256 MiB Infinity Cache
+    us = timed(lambda: tp.pack_async(srcs[0], 1, byte_t, dsts[0], n, 0, stream), n=24)
+    res["copy_64MiB_same_buffers_cache_assisted"] = {"us": round(us, 2), "gbs": round(2 * n / us / 1e3, 1)}
     del srcs, dsts
 
     # synchronous-call latency (launch + kernel + synchronize, the paper's timed region) on the small 2D vector
@@ -390,6 +407,24 @@ def other_workloads(W, tp, torch, arena, dev, stream):
                      "pack_gbs_event": round(2 * (1 << 20) / pk_ev / 1e3, 1)})
     res["sweep_1MiB"] = rows
 
+    # ---- the 64 MiB sweep with a1 held at 256 so the canonical form stays 3D (the main sweep's
+    # points all flatten to 2D because a1 reaches the 512-byte-pitch plane height)
+    rows = []
+    out64 = [torch.zeros(1 << 26, dtype=torch.uint8, device=dev) for _ in range(4)]
+    for a0 in (16, 64, 256):
+        p = W.configs.cfg2_point(a0, 1 << 26, a1_cap=256)
+        h = tp.type_from_recipe(p["recipe"])
+        span = p["alloc_bytes"]
+        nreg = max(1, min(8, (16 * GiB) // span))
+        pk = median_event_us(lambda k: tp.pack_async(arena.data_ptr() + (k % nreg) * span, 1, h, out64[k % 4], 1 << 26, 0, stream), 12)
+        plan = tp.last_plan().strip()
+        up = median_event_us(lambda k: tp.unpack_async(out64[k % 4], 1 << 26, 0, arena.data_ptr() + (k % nreg) * span, 1, h, stream), 12)
+        rows.append({"a": list(p["a"]), "pack_us": round(pk, 1), "unpack_us": round(up, 1),
+                     "pack_gbs": round(2 * (1 << 26) / pk / 1e3, 1), "unpack_gbs": round(2 * (1 << 26) / up / 1e3, 1),
+                     "plan": plan})
+    res["sweep_64MiB_3d_a1_256"] = rows
+    del out64
+
     # ---- halo: 26 regions of a 512^3 float64 grid, ghost width 3
     c3 = W.configs.cfg3()
     send = [tp.type_from_recipe(r) for r in c3["send"]]
@@ -462,7 +497,7 @@ def other_workloads(W, tp, torch, arena, dev, stream):
         p = W.configs.cfg4_point(bl)
         h = tp.type_from_recipe(p["recipe"])
         n = p["packed_bytes"]
-        for off in (0, 3):
+        for off in W.configs.CFG4_OFFSETS:
             src = lambda k: arena.data_ptr() + (k % 8) * 2 * GiB + off   # noqa: E731
             pk = median_event_us(lambda k: tp.pack_async(src(k), 1, h, outs[k % 4], n, 0, stream), 12)
             plan = tp.last_plan().strip()
