@@ -93,8 +93,9 @@ int tp_type_create_hvector(int count, int blocklength, int64_t stride_bytes, tp_
 int tp_type_create_subarray(int ndims, const int sizes[], const int subsizes[], const int starts[], int order,
                             tp_type old, tp_type *newtype);
 
-/* tp_type_commit: Sec. 3 - translate, canonicalize, convert to a StridedBlock and cache the
- * kernel plan inside the handle.  Idempotent; host only; *t is not modified.
+/* tp_type_commit: Sec. 3 - translate, canonicalize, convert to a StridedBlock and cache it in
+ * the handle (word width, tile and grid follow at call time, when the addresses and the object
+ * count are known).  Idempotent; host only; *t is not modified.
  * tp_type_free: drops the caller's reference and sets *t = TP_TYPE_NULL.  Predefined types
  * cannot be freed (TP_ERR_TYPE). */
 int tp_type_commit(tp_type *t);

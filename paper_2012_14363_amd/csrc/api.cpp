@@ -55,12 +55,7 @@ int commit_node(const TypeNode& node) {
         node.commit_status = rc;
         if (rc != kSuccess) return;
         node.block = sb;
-        uint64_t bits = static_cast<uint64_t>(sb.counts[0]) | static_cast<uint64_t>(sb.start < 0 ? -sb.start : sb.start);
-        for (int d = 1; d < sb.ndims; ++d)
-            bits |= static_cast<uint64_t>(sb.strides[d] < 0 ? -sb.strides[d] : sb.strides[d]);
-        bits |= static_cast<uint64_t>(node.extent());
-        node.type_align_log2 = bits ? std::min(4, __builtin_ctzll(bits)) : 4;
-        node.committed = true;
+        node.committed.store(true, std::memory_order_release);
     });
     return node.commit_status;
 }
@@ -71,7 +66,7 @@ TypePtr committed_node(tp_type t) {
     TypePtr node = HandleTable::instance().lookup(t);
     if (!node) return nullptr;
     if (node->kind == Kind::Named && commit_node(*node) != kSuccess) return nullptr;
-    return node->committed ? node : nullptr;
+    return node->committed.load(std::memory_order_acquire) ? node : nullptr;
 }
 
 // Resolves a data pointer to an address the GPU can use.  `allow_host`: pinned,

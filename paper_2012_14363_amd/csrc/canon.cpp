@@ -43,7 +43,7 @@ static void translate_into(const TypeNode& t, Chain& chain) {
         // order.  stride_d = extent(old) * product of the sizes of all
         // faster-varying dimensions; offset_d = start_d * stride_d.
         const int n = static_cast<int>(t.sizes.size());
-        std::vector<int64_t> pitch(n);
+        int64_t pitch[kMaxDims];
         int64_t run = t.old->extent();
         for (int k = 0; k < n; ++k) {
             const int d = t.order == 0 ? n - 1 - k : k;  // fastest dimension first
@@ -66,6 +66,7 @@ static void translate_into(const TypeNode& t, Chain& chain) {
 
 Chain translate(const TypeNode& type) {
     Chain chain;
+    chain.reserve(2 * kMaxDims);  // one allocation for all but the deepest trees
     translate_into(type, chain);
     return chain;
 }

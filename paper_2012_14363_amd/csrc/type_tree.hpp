@@ -2,6 +2,7 @@
 // size and bounds every later stage needs computed once at construction.
 #pragma once
 
+#include <atomic>
 #include <cstdint>
 #include <memory>
 #include <mutex>
@@ -27,12 +28,12 @@ struct TypeNode {
     int64_t ub = 0;    // upper bound
     int64_t extent() const { return ub - lb; }
 
-    // Filled by commit (Sec. 3: the result is cached with the datatype).
+    // Filled by commit (Sec. 3: the result is cached with the datatype).  `committed` is set
+    // last, with release order, so a thread that sees it also sees `block`.
     mutable std::once_flag commit_once;
-    mutable bool committed = false;
+    mutable std::atomic<bool> committed{false};
     mutable int commit_status = 0;
     mutable StridedBlock block;
-    mutable int type_align_log2 = 0;  // log2 of the widest word every run of the type is aligned to
 };
 
 using TypePtr = std::shared_ptr<const TypeNode>;
