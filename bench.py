@@ -57,26 +57,26 @@ def sector_bound_fraction(run: int, granule: int = 128) -> float:
 # factor a plain 64 MiB copy calibrates (FETCH_SIZE reads half the known bytes: x2; WRITE_SIZE: x1).
 # Keyed by (op, a0): (bytes fetched, bytes written).
 MEASURED_TRAFFIC = {
-    ('pack', 1): (8586295699, 68514624),
-    ('pack', 2): (4293162371, 67108864),
-    ('pack', 4): (2146595196, 67108864),
-    ('pack', 8): (1073312567, 67108864),
-    ('pack', 16): (536670805, 67108864),
-    ('pack', 32): (268348581, 67108864),
-    ('pack', 64): (134187021, 67108864),
-    ('pack', 128): (67107329, 67108864),
-    ('pack', 256): (67106817, 67108864),
+    ('pack', 1): (8586297362, 68869399),
+    ('pack', 2): (4293165442, 67080460),
+    ('pack', 4): (2146598650, 67080460),
+    ('pack', 8): (1073315254, 67080460),
+    ('pack', 16): (536674132, 67080460),
+    ('pack', 32): (268352164, 67082251),
+    ('pack', 64): (134190092, 67091207),
+    ('pack', 128): (67110143, 67114110),
+    ('pack', 256): (67109888, 67116029),
     ('pack', 512): (67108864, 67108864),
-    ('unpack', 1): (90740879, 2147483648),
-    ('unpack', 2): (67112191, 1073741824),
-    ('unpack', 4): (67111679, 536870912),
-    ('unpack', 8): (67113342, 268435456),
-    ('unpack', 16): (67113086, 134217728),
-    ('unpack', 32): (67110271, 67108864),
-    ('unpack', 64): (67110016, 67108864),
-    ('unpack', 128): (67110143, 67108864),
-    ('unpack', 256): (67109888, 67108864),
-    ('unpack', 512): (67108864, 67108864),
+    ('unpack', 1): (90937403, 2146574721),
+    ('unpack', 2): (67111679, 1073287360),
+    ('unpack', 4): (67112063, 536643680),
+    ('unpack', 8): (67113342, 268321840),
+    ('unpack', 16): (67113470, 134160920),
+    ('unpack', 32): (67111295, 67080460),
+    ('unpack', 64): (67110016, 67080460),
+    ('unpack', 128): (67109888, 67123194),
+    ('unpack', 256): (67109888, 67108352),
+    ('unpack', 512): (67108864, 67109888),
 }
 
 
