@@ -577,3 +577,47 @@ def test_model_measure_and_host_delivery(dev, tmp_path):
     assert e.value.code == tp.TP_ERR_ARG
     assert tp.pack_host(src, 3, h, host, size * 3, 0, None, 0, tp.TP_METHOD_AUTO) == (size * 3, tp.TP_METHOD_ONESHOT)
     assert np.array_equal(host.numpy(), expect[4:])
+
+
+# ------------------------------------------------------------------ maximum sizes
+def test_more_rows_than_one_launch_takes(dev):
+    # 2^31 - 1 one-byte runs at stride 2: above the 2^30 rows a launch covers, so the planner splits
+    # the outer dimension at its natural limit; numpy's strided slice is the reference
+    n = (1 << 31) - 1
+    say("max rows: generating 4 GiB")
+    src = W.fills.counter_bytes_torch(91, 2 * n, dev)
+    h = tp.type_from_recipe(vector(n, 1, 2, BYTE))
+    out = torch.zeros(n + 1, dtype=torch.uint8, device=dev)
+    say("max rows: pack")
+    assert tp.pack(src, 1, h, out, n + 1, 1) == n + 1
+    assert tp.last_plan().count("tile") >= 2, tp.last_plan()
+    got = out.cpu().numpy()
+    say("max rows: compare")
+    step = 1 << 28
+    for lo in range(0, n, step):          # compare in slices to bound host memory
+        hi = min(n, lo + step)
+        ref = W.fills.counter_bytes_numpy(91, 2 * lo, 2 * (hi - lo))[0::2]
+        assert np.array_equal(got[1 + lo:1 + hi], ref), lo
+    # the oracle itself on the first 2^20 runs
+    ref = np.zeros(1 << 20, np.uint8)
+    cc.pack(W.fills.counter_bytes_numpy(91, 0, 1 << 21), 0, 1, vector(1 << 20, 1, 2, BYTE), ref, 0)
+    assert np.array_equal(got[1:1 + (1 << 20)], ref)
+    say("max rows: unpack")
+    back = torch.full((2 * n,), 0xA5, dtype=torch.uint8, device=dev)
+    assert tp.unpack(out, n + 1, 1, back, 1, h) == n + 1
+    assert torch.equal(back[0::2], out[1:]) and bool((back[1::2] == 0xA5).all())
+
+
+def test_run_longer_than_one_launch_takes(dev):
+    # one contiguous run of 2^31 - 1 bytes between odd addresses: byte-wide words, more than the
+    # 2^30 words a launch covers along a run, so the run is cut into pieces
+    n = (1 << 31) - 1
+    say("max run: generating")
+    src = W.fills.counter_bytes_torch(92, n + 8, dev)
+    dst = torch.zeros(n + 8, dtype=torch.uint8, device=dev)
+    h = tp.type_from_recipe(contiguous(n, BYTE))
+    assert tp.pack(src.data_ptr() + 1, 1, h, dst.data_ptr() + 3, n, 0) == n
+    plan = tp.last_plan()
+    assert plan.count("tile") >= 2 and "W=1 " in plan, plan
+    assert torch.equal(dst[3:3 + n], src[1:1 + n])
+    assert int(dst[:3].sum()) == 0 and int(dst[3 + n:].sum()) == 0
