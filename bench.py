@@ -425,6 +425,27 @@ def other_workloads(W, tp, torch, arena, dev, stream):
     res["sweep_64MiB_3d_a1_256"] = rows
     del out64
 
+    # ---- 2D objects of 512-byte pitch: construction (vector or subarray) and object count must not
+    # matter (the paper's pack figure, Sec. 6.2): 4 MiB in total, runs of 64 bytes
+    rows = []
+    out4 = [torch.zeros(1 << 22, dtype=torch.uint8, device=dev) for _ in range(8)]
+    for count in (1, 16, 256):
+        nrows = (1 << 22) // 64 // count
+        variants = {
+            "vector": W.vector(nrows, 64, 512, W.BYTE),
+            "subarray": W.subarray((nrows, 512), (nrows, 64), (0, 0), "C", W.BYTE),
+        }
+        for name, recipe in variants.items():
+            h = tp.type_from_recipe(recipe)
+            span = 1 << 25
+            pk = median_event_us(lambda k: tp.pack_async(arena.data_ptr() + (k % 16) * span, count, h, out4[k % 8], 1 << 22, 0, stream), 20)
+            block = tp.type_get_strided_block(h)
+            rows.append({"construction": name, "incount": count, "object_bytes": (1 << 22) // count,
+                         "canonical": [block[1], block[2]], "extent": tp.type_get_extent(h)[1],
+                         "pack_event_us": round(pk, 1), "pack_gbs": round(2 * (1 << 22) / pk / 1e3, 1)})
+    res["objects_2d_4MiB_vector_vs_subarray"] = rows
+    del out4
+
     # ---- halo: 26 regions of a 512^3 float64 grid, ghost width 3
     c3 = W.configs.cfg3()
     send = [tp.type_from_recipe(r) for r in c3["send"]]
