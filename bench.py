@@ -321,16 +321,21 @@ def extras(W, tp, torch, np, dev, stream):
 
     # measured performance model (paper Sec. 4 / 6.3): measure the system, keep the table, and ask it
     # which way packed data should reach the host for a few shapes
-    from oracle import model as om  # only to parse the saved table for the report
     model_path = os.path.join(tempfile.mkdtemp(prefix="tp_model_"), "model.txt")
     t0 = time.perf_counter()
     tp.model_measure(stream)
     measure_s = time.perf_counter() - t0
     tp.model_save(model_path)
-    table = om.parse(open(model_path).read())
-    model = {"measure_seconds": round(measure_s, 2), "sizes": table["sizes"].tolist(), "blocks": table["blocks"].tolist()}
-    for name in om.PRIMITIVES:
-        model[name + "_us"] = np.round(table[name] * 1e6, 2).tolist()
+    # the saved table is plain text: "sizes n ...", "blocks m ...", then one line per primitive
+    lines = {ln.split()[0]: ln.split()[1:] for ln in open(model_path).read().splitlines()}
+    sizes = [float(v) for v in lines["sizes"][1:]]
+    blocks = [float(v) for v in lines["blocks"][1:]]
+    model = {"measure_seconds": round(measure_s, 2), "sizes": sizes, "blocks": blocks}
+    for name in ("gpu_pack", "gpu_unpack", "host_pack", "host_unpack"):
+        vals = np.array([float(v) for v in lines[name]]).reshape(len(sizes), len(blocks))
+        model[name + "_us"] = np.round(vals * 1e6, 2).tolist()
+    for name in ("d2h", "h2d"):
+        model[name + "_us"] = np.round(np.array([float(v) for v in lines[name]]) * 1e6, 2).tolist()
     picks = []
     for label, recipe, count in (("64 KiB in 8-byte runs", W.vector(8192, 8, 512, W.BYTE), 1),
                                  ("4 MiB in 64-byte runs", W.vector(65536, 64, 512, W.BYTE), 1),
