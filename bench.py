@@ -53,7 +53,7 @@ def sector_bound_fraction(run: int, granule: int = 128) -> float:
 
 
 # HBM bytes per launch of the sweep's kernels at 64 MiB packed, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs of this script (profiles/cfg2_sweep_64MiB_hbm_traffic.md): counter KiB x 1024 x the
+# WRITE_SIZE runs of this script (profiles/tile_kernel_strided_block_sweep_64MiB_hbm_traffic.md): counter KiB x 1024 x the
 # factor a plain 64 MiB copy calibrates (FETCH_SIZE reads half the known bytes: x2; WRITE_SIZE: x1).
 # Keyed by (op, a0): (bytes fetched, bytes written).
 MEASURED_TRAFFIC = {
@@ -203,7 +203,7 @@ def main():
                 k["hbm_traffic_frac_of_peak"] = round(sum(m) / k["avg_us"] / 1e3 / HBM_PEAK_GBS, 4)
 
     out = {
-        "metric": "pack/unpack GB/s (read+write)", "value": round(value, 2), "unit": "GB/s",
+        "metric": "pack/unpack GB/s (read+write) and % of MI355X HBM peak; canonicalize us/type", "value": round(value, 2), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(step_s * 1e3, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
         "config": {"workload": "3D strided-block sweep, a0 in {1..512}, 64 MiB packed per point, "
