@@ -12,8 +12,8 @@
 //   * each thread moves UX words along the run and UR rows, issuing all of its
 //     loads before its first store;
 //   * a row index is turned into its byte offset with multiply-shift division by
-//     the (run-time constant) dimension counts; with bx == 256 the row is uniform
-//     across the workgroup and that math runs on the scalar unit;
+//     the (run-time constant) dimension counts; in the tiles for long runs the row
+//     is uniform across the workgroup and that math runs on the scalar unit;
 //   * all parameters arrive by value in the kernel-argument segment.
 #include <hip/hip_runtime.h>
 

@@ -55,12 +55,17 @@ TP_HD inline int64_t row_offset(uint32_t r, const P& p) {
 template <int WLOG2, int UX, int UR, bool UNPACK, int NRD, class P, class Mem>
 TP_HD inline void tile_thread(const P& p, uint32_t block, uint32_t tid, Mem mem) {
     using W = typename WordOf<WLOG2>::type;
-    const uint32_t tx = tid & ((1u << p.bx_log2) - 1u);
-    const uint32_t tr = tid >> p.bx_log2;
-    const uint32_t br = static_cast<uint32_t>(kBlockThreads) >> p.bx_log2;
+    // Tiles that move more than one word per thread along the run are only planned for runs
+    // longer than the workgroup (bx == 256): every thread is then on the same row, the row
+    // index depends on the workgroup id alone and its arithmetic stays on the scalar unit.
+    constexpr bool kWholeGroupOnOneRow = UX > 1;
+    const uint32_t bx_log2 = kWholeGroupOnOneRow ? 8u : p.bx_log2;
+    const uint32_t tx = kWholeGroupOnOneRow ? tid : tid & ((1u << bx_log2) - 1u);
+    const uint32_t tr = kWholeGroupOnOneRow ? 0u : tid >> bx_log2;
+    const uint32_t br = static_cast<uint32_t>(kBlockThreads) >> bx_log2;
     const uint32_t rc = fastdiv(block, p.xc_div);
     const uint32_t xc = block - rc * p.nxc;
-    const uint32_t x0 = ((xc * UX) << p.bx_log2) + tx;
+    const uint32_t x0 = ((xc * UX) << bx_log2) + tx;
     const uint32_t r0 = rc * (br * UR) + tr;
 
     const char* src[UR][UX];
@@ -75,7 +80,7 @@ TP_HD inline void tile_thread(const P& p, uint32_t block, uint32_t tid, Mem mem)
         const int64_t poff = static_cast<int64_t>(rr) * p.row_pitch;
 #pragma unroll
         for (int ux = 0; ux < UX; ++ux) {
-            const uint32_t x = x0 + (static_cast<uint32_t>(ux) << p.bx_log2);
+            const uint32_t x = x0 + (static_cast<uint32_t>(ux) << bx_log2);
             ok[ur][ux] = row_ok && x < p.n0;
             const int64_t xb = static_cast<int64_t>(x) << WLOG2;
             const char* s = p.strided + soff + xb;
