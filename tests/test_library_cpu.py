@@ -291,16 +291,23 @@ def test_emulated_tile_shapes(a0):
 
 
 def test_emulated_word_width_follows_alignment():
-    t = vector(16, 32, 64, BYTE)
+    t = vector(16, 64, 128, BYTE)
     for shift, word in ((0, 16), (8, 8), (4, 4), (2, 2), (1, 1)):
         assert f"W={word} " in _emulate_roundtrip(t, 1, typed_shift=shift)["plan"]
         assert f"W={word} " in _emulate_roundtrip(t, 1, packed_shift=shift)["plan"]
         assert f"W={word} " in _emulate_roundtrip(t, 1, position=shift)["plan"]
     assert "W=4 " in _emulate_roundtrip(t, 1, max_word=4)["plan"]
-    assert "W=8 " in _emulate_roundtrip(vector(16, 24, 64, BYTE), 1)["plan"]
+    assert "W=16 " in _emulate_roundtrip(vector(16, 48, 64, BYTE), 1)["plan"]
+    assert "W=8 " in _emulate_roundtrip(vector(16, 40, 64, BYTE), 1)["plan"]
     assert "W=1 " in _emulate_roundtrip(vector(16, 3, 64, BYTE), 1)["plan"]
-    assert "W=2 " in _emulate_roundtrip(vector(16, 4, 6, BYTE), 1)["plan"]       # stride 6
+    assert "W=2 " in _emulate_roundtrip(vector(16, 36, 38, BYTE), 1)["plan"]     # stride 38
     assert "W=4 " in _emulate_roundtrip(vector(2, 16, 17, FLOAT), 3)["plan"]     # extent 132
+    # runs of at most 32 bytes: at least four lanes per row and at most 4-byte words, even when
+    # wider words would be aligned
+    short = lambda n: _emulate_roundtrip(vector(16, n, 64, BYTE), 1)["plan"].replace("ux=1 ur=4 nt=3 ", "")  # noqa: E731
+    assert "W=4 bx=8 " in short(32) and "W=4 bx=4 " in short(16) and "W=2 bx=4 " in short(8)
+    assert "W=1 bx=4 " in short(4) and "W=1 bx=2 " in short(2) and "W=1 bx=1 " in short(1)
+    assert "W=4 bx=8 n0=6 " in short(24) and "W=2 bx=8 n0=6 " in short(12)
 
 
 def test_emulated_launch_splitting():
