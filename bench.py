@@ -299,6 +299,21 @@ def extras(W, tp, torch, np, dev, stream):
     # the same copy without rotation: source and destination stay in the 256 MiB Infinity Cache
     us = timed(lambda: tp.pack_async(srcs[0], 1, byte_t, dsts[0], n, 0, stream), n=24)
     res["copy_64MiB_same_buffers_cache_assisted"] = {"us": round(us, 2), "gbs": round(2 * n / us / 1e3, 1)}
+    # the same 64 MiB copy between odd addresses (source + 1, destination + 3): the shifted-copy
+    # kernel against the byte-wide tile kernel it replaces
+    odd = n - 64
+
+    def unaligned():
+        tp.pack_async(srcs[k[0] % 12].data_ptr() + 1, 1, odd_t, dsts[k[0] % 12].data_ptr() + 3, odd, 0, stream)
+        k[0] += 1
+    odd_t = tp.type_from_recipe(W.contiguous(odd, W.BYTE))
+    us = timed(unaligned, n=24)
+    res["copy_64MiB_odd_addresses_shifted_copy"] = {"us": round(us, 2), "gbs": round(2 * odd / us / 1e3, 1),
+                                                   "plan": tp.last_plan().strip()}
+    tp.set_override("shift", 0)
+    us = timed(unaligned, n=12)
+    tp.set_override("shift", 1)
+    res["copy_64MiB_odd_addresses_bytewise"] = {"us": round(us, 2), "gbs": round(2 * odd / us / 1e3, 1)}
     del srcs, dsts
 
     # synchronous-call latency (launch + kernel + synchronize, the paper's timed region) on the small 2D vector

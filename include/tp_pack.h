@@ -213,6 +213,8 @@ int tp_unpack_host(const void *host_inbuf, int64_t insize, int64_t *position, vo
  *   "check_buffers" "1" (default) or "0": skip the per-call memory-residency query
  *   "nt"            "-1" (automatic) or 0..3: streaming hints, bit 0 = non-temporal loads,
  *                   bit 1 = non-temporal stores
+ *   "shift"         "1" (default) or "0": allow the shifted-copy kernel, which moves long runs
+ *                   whose two sides are not aligned alike in 4-byte words instead of bytes
  *   "max_rows_per_launch", "max_words_per_run"  1 .. 2^30: split limits (tests lower them to
  *                   exercise the multi-launch path on small inputs)
  * tp_last_plan: describes the kernel launches of the calling thread's most recent

@@ -23,6 +23,7 @@ using namespace tp;
 
 std::atomic<int> g_max_word_log2{4};
 std::atomic<int> g_nt{-1};
+std::atomic<bool> g_allow_shift{true};
 std::atomic<bool> g_check_buffers{true};
 std::atomic<int64_t> g_max_rows_per_launch{int64_t{1} << 30};
 std::atomic<int64_t> g_max_words_per_run{int64_t{1} << 30};
@@ -145,6 +146,7 @@ int plan_request(const TypeNode& node, const void* typed_buf, int64_t count, Pac
     in.packed = const_cast<char*>(packed->view) + position;
     in.max_word_log2 = g_max_word_log2.load(std::memory_order_relaxed);
     in.nt = g_nt.load(std::memory_order_relaxed);
+    in.allow_shift = g_allow_shift.load(std::memory_order_relaxed);
     in.max_rows_per_launch = g_max_rows_per_launch.load(std::memory_order_relaxed);
     in.max_words_per_run = g_max_words_per_run.load(std::memory_order_relaxed);
     std::vector<Launch> mine;
@@ -416,6 +418,11 @@ int tp_set_override(const char* key, const char* value) {
     if (!std::strcmp(key, "nt")) {
         if (v < -1 || v > 3) return kErrArg;
         g_nt.store(static_cast<int>(v));
+        return kSuccess;
+    }
+    if (!std::strcmp(key, "shift")) {
+        if (v != 0 && v != 1) return kErrArg;
+        g_allow_shift.store(v == 1);
         return kSuccess;
     }
     if (!std::strcmp(key, "check_buffers")) {

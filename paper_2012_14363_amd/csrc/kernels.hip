@@ -36,6 +36,11 @@ struct DeviceMem {
         if constexpr (NT & 1) return __builtin_nontemporal_load(reinterpret_cast<const W*>(p));
         else return *reinterpret_cast<const W*>(p);
     }
+    // a load that may cover bytes next to the run (inside the same aligned word)
+    template <class W>
+    __device__ __forceinline__ W load_straddling(const char* p) const {
+        return load<W>(p);
+    }
     template <class W>
     __device__ __forceinline__ void store(char* p, const W& v) const {
         if constexpr (NT & 2) __builtin_nontemporal_store(v, reinterpret_cast<W*>(p));
@@ -46,6 +51,13 @@ struct DeviceMem {
 template <int WLOG2, int UX, int UR, bool UNPACK, int NRD, int NT>
 __global__ void __launch_bounds__(kBlockThreads) tile_kernel(const KParams p) {
     tile_thread<WLOG2, UX, UR, UNPACK, NRD>(p, blockIdx.x, threadIdx.x, DeviceMem<NT>{});
+}
+
+// Long runs with unlike alignment on the two sides: aligned 4-byte words on both sides, the
+// source re-aligned in registers (tile_body.hpp: shift_thread).
+template <int UX, int UR, bool UNPACK, int NRD>
+__global__ void __launch_bounds__(kBlockThreads) shift_kernel(const KParams p) {
+    shift_thread<UX, UR, UNPACK, NRD>(p, blockIdx.x, threadIdx.x, DeviceMem<3>{});
 }
 
 // Many planned launches, of different datatypes, as one grid: a workgroup looks up
@@ -74,12 +86,29 @@ struct PickKernel {
     }
 };
 
+template <bool UNPACK>
+struct PickShiftKernel {
+    KernelFn fn = nullptr;
+    template <int WLOG2, int UX, int UR, int NRD>
+    void operator()() {
+        fn = shift_kernel<UX, UR, UNPACK, NRD>;
+    }
+};
+
 }  // namespace
 
 hipError_t enqueue(const Launch& l, bool unpack, hipStream_t stream) {
     const KParams p = kernel_params(l);
     KernelFn fn = nullptr;
-    if (unpack) {
+    if (l.kind == kShift) {
+        if (unpack) {
+            PickShiftKernel<true> pick;
+            if (dispatch_variant(2, l.ux, l.ur, p.nrd, pick)) fn = pick.fn;
+        } else {
+            PickShiftKernel<false> pick;
+            if (dispatch_variant(2, l.ux, l.ur, p.nrd, pick)) fn = pick.fn;
+        }
+    } else if (unpack) {
         PickKernel<true> pick;
         pick.nt = l.nt;
         if (dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, pick)) fn = pick.fn;

@@ -40,6 +40,7 @@ void choose_tile(uint32_t n0, Launch* l) {
 
 struct Splitter {
     const PlanInput& in;
+    int kind;
     int word_log2;
     int64_t row_pitch;  // bytes of a full run in the packed stream
     std::vector<Launch>* out;
@@ -47,12 +48,14 @@ struct Splitter {
     // One launch over dims[0..nd): dims[0].count bytes per run (a multiple of the word).
     void add(const std::vector<Dim>& dims, const char* typed, char* packed) {
         Launch l;
+        l.kind = kind;
         l.word_log2 = word_log2;
         KParams& p = l.p;
         p.strided = typed;
         p.packed = packed;
         p.row_pitch = row_pitch;
-        p.n0 = static_cast<uint32_t>(dims[0].count >> word_log2);
+        p.run_len = static_cast<uint32_t>(dims[0].count);
+        p.n0 = slots(dims[0].count);
         uint64_t rows = 1;
         p.nrd = 0;
         for (size_t d = 1; d < dims.size(); ++d) {
@@ -75,6 +78,12 @@ struct Splitter {
         out->push_back(l);
     }
 
+    // Lane slots along a run of `bytes`: words, or for a shifted copy the whole 4-byte words of
+    // the destination plus one slot for the ragged head and tail bytes.
+    uint32_t slots(int64_t bytes) const {
+        return static_cast<uint32_t>(kind == kShift ? (bytes >> 2) + 1 : bytes >> word_log2);
+    }
+
     // Largest row count for which block ids stay below 2^30 with runs of n0 words.
     int64_t row_limit(int64_t n0) const {
         Launch probe;
@@ -90,7 +99,7 @@ struct Splitter {
     void split_rows(std::vector<Dim> dims, const char* typed, char* packed) {
         int64_t rows = 1;
         for (size_t d = 1; d < dims.size(); ++d) rows *= dims[d].count;
-        const int64_t limit = row_limit(dims[0].count >> word_log2);
+        const int64_t limit = row_limit(slots(dims[0].count));
         if (rows <= limit) {
             add(dims, typed, packed);
             return;
@@ -154,12 +163,20 @@ int plan_launches(const PlanInput& in, std::vector<Launch>* out) {
         word_log2 = std::min(word_log2, std::min(2, quarter_log2));
     }
 
-    Splitter s{in, word_log2, dims[0].count, out};
+    // Long runs that only byte- or 2-byte-wide words would fit move through the shifted copy.
+    int kind = kTile;
+    if (in.allow_shift && word_log2 < 2 && in.max_word_log2 >= 2 && dims[0].count >= 64) {
+        kind = kShift;
+        word_log2 = 2;
+    }
+    Splitter s{in, kind, word_log2, dims[0].count, out};
     s.split_runs(dims, typed, in.packed);
     return kSuccess;
 }
 
-bool batchable(const Launch& l) { return l.p.nrd <= static_cast<uint32_t>(kBatchRowDims) && l.nblocks > 0; }
+bool batchable(const Launch& l) {
+    return l.kind == kTile && l.p.nrd <= static_cast<uint32_t>(kBatchRowDims) && l.nblocks > 0;
+}
 
 void make_batches(const std::vector<Launch>& launches, std::vector<BatchParams>* batches,
                   std::vector<Launch>* singles) {
@@ -220,8 +237,8 @@ std::string describe(const std::vector<Launch>& launches) {
     std::string text;
     char line[256];
     for (const Launch& l : launches) {
-        std::snprintf(line, sizeof line, "tile W=%d ux=%d ur=%d nt=%d bx=%u n0=%u rows=%u nrd=%u blocks=%u\n",
-                      1 << l.word_log2, l.ux, l.ur, l.nt, 1u << l.p.bx_log2, l.p.n0, l.p.nrows, l.p.nrd, l.nblocks);
+        std::snprintf(line, sizeof line, "%s W=%d ux=%d ur=%d nt=%d bx=%u n0=%u rows=%u nrd=%u blocks=%u\n",
+                      l.kind == kShift ? "shift" : "tile", 1 << l.word_log2, l.ux, l.ur, l.nt, 1u << l.p.bx_log2, l.p.n0, l.p.nrows, l.p.nrd, l.nblocks);
         text += line;
     }
     return text;

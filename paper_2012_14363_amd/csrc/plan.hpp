@@ -29,14 +29,21 @@ struct KParams {
     uint32_t bx_log2 = 0;           // lanes along a run = 1 << bx_log2; the other lanes take further rows
     uint32_t nxc = 1;               // x-chunks per row; block id = row_chunk * nxc + x_chunk
     uint32_t nrd = 0;               // row dimensions in use
+    uint32_t run_len = 0;           // shifted-copy launches: bytes per run (n0 = run_len / 4 + 1 slots)
     FastDiv xc_div;
     FastDiv rdiv[kMaxDims];
     uint32_t rcount[kMaxDims] = {};
     int64_t rstride[kMaxDims] = {};
 };
 
+// kTile: every access is naturally aligned on both sides with one word width.
+// kShift: long runs whose two sides are not aligned alike (odd addresses, odd run lengths):
+// 4-byte words on both sides, re-aligned in registers (see shift_thread).
+enum LaunchKind : int { kTile = 0, kShift = 1 };
+
 struct Launch {
     KParams p;
+    int kind = kTile;
     int word_log2 = 0;  // W = 1 << word_log2 bytes per lane access
     int ux = 1;         // words per thread along the run
     int ur = 1;         // rows per thread
@@ -52,6 +59,7 @@ struct PlanInput {
     char* packed = nullptr;        // contiguous buffer + position
     int max_word_log2 = 4;   // override: cap on the access width
     int nt = -1;             // override: streaming hints (-1 = planner's choice)
+    bool allow_shift = true; // override: permit the shifted-copy kernel
     int64_t max_rows_per_launch = int64_t{1} << 30;   // tests lower these to force splitting
     int64_t max_words_per_run = int64_t{1} << 30;
 };

@@ -102,6 +102,87 @@ TP_HD inline void tile_thread(const P& p, uint32_t block, uint32_t tid, Mem mem)
             if (ok[ur][ux]) mem.template store<W>(dst[ur][ux], v[ur][ux]);
 }
 
+// ------------------------------------------------------------------ shifted copy
+// Runs whose source and destination are not aligned alike (odd addresses, odd run lengths)
+// would otherwise move byte by byte.  Here the destination row is cut into a head of 0-3
+// bytes up to its first 4-byte boundary, whole aligned 4-byte words, and a tail of 0-3 bytes.
+// Lane x < nb builds destination word x from the two aligned source words that straddle it
+// (a funnel shift by the rows' relative misalignment, 0-3 bytes) and stores it aligned; lane
+// x == nb copies the head and tail bytes.  Every store is exact: no byte outside the run is
+// written.  A source load may cover up to 3 bytes outside the run, but always inside an
+// aligned word that also holds a byte of the run, hence inside a mapped page.
+TP_HD inline uint32_t funnel_shift_bytes(uint32_t lo, uint32_t hi, uint32_t bytes) {
+    return static_cast<uint32_t>(((static_cast<uint64_t>(hi) << 32) | lo) >> (8u * bytes));
+}
+
+template <int UX, int UR, bool UNPACK, int NRD, class P, class Mem>
+TP_HD inline void shift_thread(const P& p, uint32_t block, uint32_t tid, Mem mem) {
+    constexpr bool kWholeGroupOnOneRow = UX > 1;
+    const uint32_t bx_log2 = kWholeGroupOnOneRow ? 8u : p.bx_log2;
+    const uint32_t tx = kWholeGroupOnOneRow ? tid : tid & ((1u << bx_log2) - 1u);
+    const uint32_t tr = kWholeGroupOnOneRow ? 0u : tid >> bx_log2;
+    const uint32_t br = static_cast<uint32_t>(kBlockThreads) >> bx_log2;
+    const uint32_t rc = fastdiv(block, p.xc_div);
+    const uint32_t xc = block - rc * p.nxc;
+    const uint32_t x0 = ((xc * UX) << bx_log2) + tx;
+    const uint32_t r0 = rc * (br * UR) + tr;
+    const uint32_t len = p.run_len;
+
+    const char* src_word[UR][UX];  // aligned source word below the destination word's first byte
+    char* dst_word[UR][UX];
+    uint32_t shift[UR];
+    int role[UR][UX];  // 0: idle, 1: whole word, 2: head and tail bytes
+    const char* src_row[UR];
+    char* dst_row[UR];
+    uint32_t head[UR], body_words[UR];
+#pragma unroll
+    for (int ur = 0; ur < UR; ++ur) {
+        const uint32_t r = r0 + ur * br;
+        const bool row_ok = r < p.nrows;
+        const uint32_t rr = row_ok ? r : 0u;
+        const char* s = p.strided + row_offset<NRD>(rr, p);
+        char* q = p.packed + static_cast<int64_t>(rr) * p.row_pitch;
+        src_row[ur] = UNPACK ? q : s;
+        dst_row[ur] = UNPACK ? const_cast<char*>(s) : q;
+        const uint32_t to_boundary = static_cast<uint32_t>(-reinterpret_cast<uintptr_t>(dst_row[ur])) & 3u;
+        head[ur] = to_boundary < len ? to_boundary : len;
+        body_words[ur] = (len - head[ur]) >> 2;
+        const uintptr_t first = reinterpret_cast<uintptr_t>(src_row[ur]) + head[ur];
+        shift[ur] = static_cast<uint32_t>(first & 3u);
+#pragma unroll
+        for (int ux = 0; ux < UX; ++ux) {
+            const uint32_t x = x0 + (static_cast<uint32_t>(ux) << bx_log2);
+            role[ur][ux] = !row_ok ? 0 : x < body_words[ur] ? 1 : x == body_words[ur] ? 2 : 0;
+            const int64_t xb = static_cast<int64_t>(x) << 2;
+            src_word[ur][ux] = src_row[ur] + head[ur] - shift[ur] + xb;
+            dst_word[ur][ux] = dst_row[ur] + head[ur] + xb;
+        }
+    }
+    uint32_t v[UR][UX];
+#pragma unroll
+    for (int ur = 0; ur < UR; ++ur)
+#pragma unroll
+        for (int ux = 0; ux < UX; ++ux)
+            if (role[ur][ux] == 1) {
+                const uint32_t lo = mem.template load_straddling<uint32_t>(src_word[ur][ux]);
+                // with no misalignment the next word is not needed (and may lie past the run)
+                const uint32_t hi = shift[ur] ? mem.template load_straddling<uint32_t>(src_word[ur][ux] + 4) : 0u;
+                v[ur][ux] = funnel_shift_bytes(lo, hi, shift[ur]);
+            }
+#pragma unroll
+    for (int ur = 0; ur < UR; ++ur)
+#pragma unroll
+        for (int ux = 0; ux < UX; ++ux) {
+            if (role[ur][ux] == 1) mem.template store<uint32_t>(dst_word[ur][ux], v[ur][ux]);
+            if (role[ur][ux] == 2) {
+                for (uint32_t k = 0; k < head[ur]; ++k)
+                    mem.template store<uint8_t>(dst_row[ur] + k, mem.template load<uint8_t>(src_row[ur] + k));
+                for (uint32_t k = head[ur] + 4u * body_words[ur]; k < len; ++k)
+                    mem.template store<uint8_t>(dst_row[ur] + k, mem.template load<uint8_t>(src_row[ur] + k));
+            }
+        }
+}
+
 // Calls f.template operator()<WLOG2, UX, UR, NRD>() for the variant a launch names;
 // returns false if there is none.  nrd 0 and 1 share the division-free variant
 // (the caller gives a single row one dummy dimension).

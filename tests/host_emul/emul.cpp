@@ -41,6 +41,20 @@ struct HostMem {
         std::memcpy(&v, p, sizeof(W));
         return v;
     }
+    // A load allowed to cover bytes next to the buffer as long as the aligned word also holds a
+    // byte inside it (on the device such a word lies in a mapped page); outside bytes read as 0.
+    template <class W>
+    W load_straddling(const char* p) const {
+        if (reinterpret_cast<uintptr_t>(p) % sizeof(W)) c->misaligned++;
+        unsigned char bytes[sizeof(W)] = {};
+        bool any = false;
+        for (size_t i = 0; i < sizeof(W); ++i)
+            if (inside(p + i, 1)) { bytes[i] = static_cast<unsigned char>(p[i]); any = true; }
+        if (!any) c->oob++;
+        W v;
+        std::memcpy(&v, bytes, sizeof(W));
+        return v;
+    }
     template <class W>
     void store(char* p, const W& v) const {
         if (!inside(p, sizeof(W))) { c->oob++; return; }
@@ -57,11 +71,14 @@ struct RunLaunch {
     const tp::KParams* p;
     uint32_t nblocks;
     HostMem mem;
+    int kind = tp::kTile;
     template <int WLOG2, int UX, int UR, int NRD>
     void operator()() {
         for (uint32_t b = 0; b < nblocks; ++b)
-            for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t)
-                tp::tile_thread<WLOG2, UX, UR, UNPACK, NRD>(*p, b, t, mem);
+            for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t) {
+                if (kind == tp::kShift) tp::shift_thread<UX, UR, UNPACK, NRD>(*p, b, t, mem);
+                else tp::tile_thread<WLOG2, UX, UR, UNPACK, NRD>(*p, b, t, mem);
+            }
     }
 };
 
@@ -80,8 +97,8 @@ extern "C" {
 int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, const int64_t* strides, int64_t extent,
                   int64_t count, char* typed_buf, int64_t typed_len, int64_t origin, char* packed_buf,
                   int64_t packed_len, int64_t position, int max_word_log2, int64_t max_rows_per_launch,
-                  int64_t max_words_per_run, uint8_t* write_count, int64_t* result, char* plan_text,
-                  int64_t plan_text_len) {
+                  int64_t max_words_per_run, int allow_shift, uint8_t* write_count, int64_t* result,
+                  char* plan_text, int64_t plan_text_len) {
     tp::PlanInput in;
     in.block.ndims = ndims;
     in.block.start = start;
@@ -96,6 +113,7 @@ int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, c
     in.max_word_log2 = max_word_log2;
     in.max_rows_per_launch = max_rows_per_launch;
     in.max_words_per_run = max_words_per_run;
+    in.allow_shift = allow_shift != 0;
     std::vector<tp::Launch> launches;
     const int rc = tp::plan_launches(in, &launches);
     if (rc != tp::kSuccess) return rc;
@@ -109,10 +127,10 @@ int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, c
         const tp::KParams p = tp::kernel_params(l);
         bool found;
         if (unpack) {
-            RunLaunch<true> run{&p, l.nblocks, HostMem{&c}};
+            RunLaunch<true> run{&p, l.nblocks, HostMem{&c}, l.kind};
             found = tp::dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, run);
         } else {
-            RunLaunch<false> run{&p, l.nblocks, HostMem{&c}};
+            RunLaunch<false> run{&p, l.nblocks, HostMem{&c}, l.kind};
             found = tp::dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, run);
         }
         if (!found) return 100;
@@ -197,10 +215,10 @@ int emul_transfer_batch(int unpack, int n, const int* ndims, const int64_t* star
         const tp::KParams p = tp::kernel_params(l);
         bool found;
         if (unpack) {
-            RunLaunch<true> run{&p, l.nblocks, HostMem{&c}};
+            RunLaunch<true> run{&p, l.nblocks, HostMem{&c}, l.kind};
             found = tp::dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, run);
         } else {
-            RunLaunch<false> run{&p, l.nblocks, HostMem{&c}};
+            RunLaunch<false> run{&p, l.nblocks, HostMem{&c}, l.kind};
             found = tp::dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, run);
         }
         if (!found) return 100;

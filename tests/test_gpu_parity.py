@@ -101,6 +101,28 @@ def test_tile_shapes_and_ragged_tails(dev, a0):
     roundtrip(vector(1031, a0, a0 + 16, BYTE), 1, dev, seed=a0 + 1)
 
 
+@pytest.mark.parametrize("run", [64, 67, 127, 1030, 4049, 70001])
+def test_shifted_copy_for_unlike_alignment(dev, run):
+    # long runs at odd addresses / odd lengths take the shifted-copy kernel; every relative
+    # misalignment of the two sides, exact writes (poisoned gaps), 2D and 3D
+    say("shifted copy, run", run)
+    rng = random.Random(run)
+    for ts in range(4):
+        for ps in (0, 1, 2, 3):
+            roundtrip(vector(41, run, run + rng.choice((1, 3, 5, 61)), BYTE), rng.randint(1, 2), dev,
+                      typed_shift=ts, packed_shift=ps, position=rng.randint(0, 3), seed=run + ts)
+            assert tp.last_plan().startswith("shift W=4 "), tp.last_plan()
+    roundtrip(hvector(3, 1, 9 * (run + 7), hvector(9, 1, run + 7, contiguous(run, BYTE))), 2, dev,
+              typed_shift=3, packed_shift=1, seed=run)
+    assert "shift" in tp.last_plan()
+    try:   # and with the kernel switched off the byte-wide tile kernel gives the same bytes
+        tp.set_override("shift", 0)
+        roundtrip(vector(41, run, run + 3, BYTE), 1, dev, typed_shift=1, seed=run)
+        assert "tile W=1 " in tp.last_plan()
+    finally:
+        tp.set_override("shift", 1)
+
+
 def test_word_widths_forced(dev):
     t = vector(300, 64, 96, BYTE)
     try:

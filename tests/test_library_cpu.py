@@ -293,14 +293,14 @@ def test_emulated_tile_shapes(a0):
 def test_emulated_word_width_follows_alignment():
     t = vector(16, 64, 128, BYTE)
     for shift, word in ((0, 16), (8, 8), (4, 4), (2, 2), (1, 1)):
-        assert f"W={word} " in _emulate_roundtrip(t, 1, typed_shift=shift)["plan"]
-        assert f"W={word} " in _emulate_roundtrip(t, 1, packed_shift=shift)["plan"]
-        assert f"W={word} " in _emulate_roundtrip(t, 1, position=shift)["plan"]
+        assert f"tile W={word} " in _emulate_roundtrip(t, 1, typed_shift=shift, allow_shift=False)["plan"]
+        assert f"tile W={word} " in _emulate_roundtrip(t, 1, packed_shift=shift, allow_shift=False)["plan"]
+        assert f"tile W={word} " in _emulate_roundtrip(t, 1, position=shift, allow_shift=False)["plan"]
     assert "W=4 " in _emulate_roundtrip(t, 1, max_word=4)["plan"]
     assert "W=16 " in _emulate_roundtrip(vector(16, 48, 64, BYTE), 1)["plan"]
     assert "W=8 " in _emulate_roundtrip(vector(16, 40, 64, BYTE), 1)["plan"]
     assert "W=1 " in _emulate_roundtrip(vector(16, 3, 64, BYTE), 1)["plan"]
-    assert "W=2 " in _emulate_roundtrip(vector(16, 36, 38, BYTE), 1)["plan"]     # stride 38
+    assert "tile W=2 " in _emulate_roundtrip(vector(16, 36, 38, BYTE), 1)["plan"]     # stride 38
     assert "W=4 " in _emulate_roundtrip(vector(2, 16, 17, FLOAT), 3)["plan"]     # extent 132
     # runs of at most 32 bytes: at least four lanes per row and at most 4-byte words, even when
     # wider words would be aligned
@@ -308,6 +308,33 @@ def test_emulated_word_width_follows_alignment():
     assert "W=4 bx=8 " in short(32) and "W=4 bx=4 " in short(16) and "W=2 bx=4 " in short(8)
     assert "W=1 bx=4 " in short(4) and "W=1 bx=2 " in short(2) and "W=1 bx=1 " in short(1)
     assert "W=4 bx=8 n0=6 " in short(24) and "W=2 bx=8 n0=6 " in short(12)
+
+
+def test_emulated_shifted_copy_for_unlike_alignment():
+    # runs of 64 bytes or more that only byte- or 2-byte-wide words would fit go through the
+    # shifted copy: exact bytes written once, gaps untouched, any relative misalignment
+    rng = random.Random(404)
+    for run in (64, 65, 66, 67, 100, 127, 255, 1023, 1030, 4049):
+        for _ in range(3):
+            stride = run + rng.choice((1, 3, 5, 7, 9, 62))
+            res = _emulate_roundtrip(vector(rng.randint(2, 9), run, stride, BYTE), rng.randint(1, 2),
+                                     typed_shift=rng.randint(0, 7), packed_shift=rng.randint(0, 7),
+                                     position=rng.randint(0, 5))
+            assert res["plan"].startswith("shift W=4 "), res["plan"]
+    # every relative misalignment of the two sides, 3D, ragged run, several tiles
+    t = hvector(3, 1, 7 * 5003, hvector(7, 1, 5003, contiguous(4099, BYTE)))
+    for ts in range(4):
+        for ps in range(4):
+            assert "shift" in _emulate_roundtrip(t, 1, typed_shift=ts, packed_shift=ps, position=1)["plan"]
+    # aligned alike on both sides but at an odd address: still the shifted copy (4-byte words)
+    assert "shift" in _emulate_roundtrip(contiguous(3000, BYTE), 1, typed_shift=1, packed_shift=1)["plan"]
+    # short runs and 4-byte-aligned data keep the plain tile kernel; the override switches it off
+    assert "tile W=1 " in _emulate_roundtrip(vector(9, 63, 71, BYTE), 1, typed_shift=1)["plan"]
+    assert "tile W=4 " in _emulate_roundtrip(vector(9, 68, 72, BYTE), 1, typed_shift=4)["plan"]
+    assert "tile W=1 " in _emulate_roundtrip(vector(9, 67, 71, BYTE), 1, allow_shift=False)["plan"]
+    # run pieces (a run cut along its length) each get their own head and tail
+    res = _emulate_roundtrip(vector(3, 1001, 1013, BYTE), 2, typed_shift=3, max_words_per_run=50)
+    assert res["launches"] > 4 and "shift" in res["plan"]
 
 
 def test_emulated_launch_splitting():
