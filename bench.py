@@ -57,26 +57,26 @@ def sector_bound_fraction(run: int, granule: int = 128) -> float:
 # factor a plain 64 MiB copy calibrates (FETCH_SIZE reads half the known bytes: x2; WRITE_SIZE: x1).
 # Keyed by (op, a0): (bytes fetched, bytes written).
 MEASURED_TRAFFIC = {
-    ('pack', 1): (8586297362, 68869399),
-    ('pack', 2): (4293165442, 67080460),
-    ('pack', 4): (2146598650, 67080460),
-    ('pack', 8): (1073315254, 67080460),
-    ('pack', 16): (536674132, 67080460),
-    ('pack', 32): (268352164, 67082251),
-    ('pack', 64): (134190092, 67091207),
-    ('pack', 128): (67110143, 67114110),
-    ('pack', 256): (67109888, 67116029),
+    ('pack', 1): (8587083965, 68945041),
+    ('pack', 2): (4293576915, 69172964),
+    ('pack', 4): (2146811106, 70657245),
+    ('pack', 8): (1073418349, 67076751),
+    ('pack', 16): (536718003, 67080590),
+    ('pack', 32): (268371350, 67078926),
+    ('pack', 64): (134203269, 67087754),
+    ('pack', 128): (67116286, 67125880),
+    ('pack', 256): (67116030, 67115773),
     ('pack', 512): (67108864, 67108864),
-    ('unpack', 1): (90937403, 2146574721),
-    ('unpack', 2): (67111679, 1073287360),
-    ('unpack', 4): (67112063, 536643680),
-    ('unpack', 8): (67113342, 268321840),
-    ('unpack', 16): (67113470, 134160920),
-    ('unpack', 32): (67111295, 67080460),
-    ('unpack', 64): (67110016, 67080460),
-    ('unpack', 128): (67109888, 67123194),
-    ('unpack', 256): (67109888, 67108352),
-    ('unpack', 512): (67108864, 67109888),
+    ('unpack', 1): (90063590, 2146456044),
+    ('unpack', 2): (75308096, 1073228022),
+    ('unpack', 4): (67276616, 536614011),
+    ('unpack', 8): (67117181, 268307005),
+    ('unpack', 16): (67109760, 134153503),
+    ('unpack', 32): (67109504, 67076751),
+    ('unpack', 64): (67108992, 67076751),
+    ('unpack', 128): (67108992, 67132277),
+    ('unpack', 256): (67108992, 67120890),
+    ('unpack', 512): (67112959, 67115645),
 }
 
 
