@@ -71,27 +71,23 @@ __global__ void __launch_bounds__(kBlockThreads) batch_kernel(const BatchParams 
 
 using KernelFn = void (*)(const KParams);
 
+// Visitor for dispatch_launch: the kernel instantiation a launch names.
 template <bool UNPACK>
 struct PickKernel {
-    int nt = 0;
+    int nt = 3;
     KernelFn fn = nullptr;
-    template <int WLOG2, int UX, int UR, int NRD>
+    template <int KIND, int WLOG2, int UX, int UR, int NRD>
     void operator()() {
-        switch (nt) {
-        case 0: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 0>; break;
-        case 1: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 1>; break;
-        case 2: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 2>; break;
-        default: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 3>; break;
+        if constexpr (KIND == kShift) {
+            fn = shift_kernel<UX, UR, UNPACK, NRD>;
+        } else {
+            switch (nt) {
+            case 0: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 0>; break;
+            case 1: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 1>; break;
+            case 2: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 2>; break;
+            default: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 3>; break;
+            }
         }
-    }
-};
-
-template <bool UNPACK>
-struct PickShiftKernel {
-    KernelFn fn = nullptr;
-    template <int WLOG2, int UX, int UR, int NRD>
-    void operator()() {
-        fn = shift_kernel<UX, UR, UNPACK, NRD>;
     }
 };
 
@@ -100,22 +96,14 @@ struct PickShiftKernel {
 hipError_t enqueue(const Launch& l, bool unpack, hipStream_t stream) {
     const KParams p = kernel_params(l);
     KernelFn fn = nullptr;
-    if (l.kind == kShift) {
-        if (unpack) {
-            PickShiftKernel<true> pick;
-            if (dispatch_variant(2, l.ux, l.ur, p.nrd, pick)) fn = pick.fn;
-        } else {
-            PickShiftKernel<false> pick;
-            if (dispatch_variant(2, l.ux, l.ur, p.nrd, pick)) fn = pick.fn;
-        }
-    } else if (unpack) {
+    if (unpack) {
         PickKernel<true> pick;
         pick.nt = l.nt;
-        if (dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, pick)) fn = pick.fn;
+        if (dispatch_launch(l, p.nrd, pick)) fn = pick.fn;
     } else {
         PickKernel<false> pick;
         pick.nt = l.nt;
-        if (dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, pick)) fn = pick.fn;
+        if (dispatch_launch(l, p.nrd, pick)) fn = pick.fn;
     }
     if (!fn || l.nblocks == 0) return hipErrorInvalidValue;
     hipLaunchKernelGGL(fn, dim3(l.nblocks), dim3(kBlockThreads), 0, stream, p);

@@ -81,7 +81,7 @@ struct Splitter {
     // Lane slots along a run of `bytes`: words, or for a shifted copy the whole 4-byte words of
     // the destination plus one slot for the ragged head and tail bytes.
     uint32_t slots(int64_t bytes) const {
-        return static_cast<uint32_t>(kind == kShift ? (bytes >> 2) + 1 : bytes >> word_log2);
+        return static_cast<uint32_t>(kind == kShift ? (bytes >> word_log2) + 1 : bytes >> word_log2);
     }
 
     // Largest row count for which block ids stay below 2^30 with runs of n0 words.
@@ -117,7 +117,9 @@ struct Splitter {
 
     // Runs longer than the per-launch word limit are cut into pieces along dimension 0.
     void split_runs(const std::vector<Dim>& dims, const char* typed, char* packed) {
-        const int64_t piece = in.max_words_per_run << word_log2;
+        // a shifted-copy piece also has to keep its byte length in 32 bits
+        const int64_t piece = kind == kShift ? std::min(in.max_words_per_run << word_log2, int64_t{1} << 30)
+                                             : in.max_words_per_run << word_log2;
         for (int64_t off = 0; off < dims[0].count; off += piece) {
             std::vector<Dim> sub = dims;
             sub[0].count = std::min(piece, dims[0].count - off);

@@ -66,17 +66,17 @@ struct HostMem {
     }
 };
 
+// Visitor for dispatch_launch: run every workgroup and thread of the variant a launch names.
 template <bool UNPACK>
 struct RunLaunch {
     const tp::KParams* p;
     uint32_t nblocks;
     HostMem mem;
-    int kind = tp::kTile;
-    template <int WLOG2, int UX, int UR, int NRD>
+    template <int KIND, int WLOG2, int UX, int UR, int NRD>
     void operator()() {
         for (uint32_t b = 0; b < nblocks; ++b)
             for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t) {
-                if (kind == tp::kShift) tp::shift_thread<UX, UR, UNPACK, NRD>(*p, b, t, mem);
+                if constexpr (KIND == tp::kShift) tp::shift_thread<UX, UR, UNPACK, NRD>(*p, b, t, mem);
                 else tp::tile_thread<WLOG2, UX, UR, UNPACK, NRD>(*p, b, t, mem);
             }
     }
@@ -127,11 +127,11 @@ int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, c
         const tp::KParams p = tp::kernel_params(l);
         bool found;
         if (unpack) {
-            RunLaunch<true> run{&p, l.nblocks, HostMem{&c}, l.kind};
-            found = tp::dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, run);
+            RunLaunch<true> run{&p, l.nblocks, HostMem{&c}};
+            found = tp::dispatch_launch(l, p.nrd, run);
         } else {
-            RunLaunch<false> run{&p, l.nblocks, HostMem{&c}, l.kind};
-            found = tp::dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, run);
+            RunLaunch<false> run{&p, l.nblocks, HostMem{&c}};
+            found = tp::dispatch_launch(l, p.nrd, run);
         }
         if (!found) return 100;
     }
@@ -215,11 +215,11 @@ int emul_transfer_batch(int unpack, int n, const int* ndims, const int64_t* star
         const tp::KParams p = tp::kernel_params(l);
         bool found;
         if (unpack) {
-            RunLaunch<true> run{&p, l.nblocks, HostMem{&c}, l.kind};
-            found = tp::dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, run);
+            RunLaunch<true> run{&p, l.nblocks, HostMem{&c}};
+            found = tp::dispatch_launch(l, p.nrd, run);
         } else {
-            RunLaunch<false> run{&p, l.nblocks, HostMem{&c}, l.kind};
-            found = tp::dispatch_variant(l.word_log2, l.ux, l.ur, p.nrd, run);
+            RunLaunch<false> run{&p, l.nblocks, HostMem{&c}};
+            found = tp::dispatch_launch(l, p.nrd, run);
         }
         if (!found) return 100;
     }

@@ -107,8 +107,8 @@ def test_shifted_copy_for_unlike_alignment(dev, run):
     # misalignment of the two sides, exact writes (poisoned gaps), 2D and 3D
     say("shifted copy, run", run)
     rng = random.Random(run)
-    for ts in range(4):
-        for ps in (0, 1, 2, 3):
+    for ts in (0, 1, 2, 3, 7, 13):
+        for ps in (0, 1, 2, 3, 6, 15):
             roundtrip(vector(41, run, run + rng.choice((1, 3, 5, 61)), BYTE), rng.randint(1, 2), dev,
                       typed_shift=ts, packed_shift=ps, position=rng.randint(0, 3), seed=run + ts)
             assert tp.last_plan().startswith("shift W=4 "), tp.last_plan()
@@ -631,14 +631,25 @@ def test_more_rows_than_one_launch_takes(dev):
 
 
 def test_run_longer_than_one_launch_takes(dev):
-    # one contiguous run of 2^31 - 1 bytes between odd addresses: byte-wide words, more than the
-    # 2^30 words a launch covers along a run, so the run is cut into pieces
+    # one contiguous run of 2^31 - 1 bytes between odd addresses.  The shifted copy cuts it into
+    # pieces of 2^30 bytes; with that kernel switched off it moves in byte-wide words, more than the
+    # 2^30 words a launch covers along a run, so the run is cut into pieces as well
     n = (1 << 31) - 1
     say("max run: generating")
     src = W.fills.counter_bytes_torch(92, n + 8, dev)
     dst = torch.zeros(n + 8, dtype=torch.uint8, device=dev)
     h = tp.type_from_recipe(contiguous(n, BYTE))
     assert tp.pack(src.data_ptr() + 1, 1, h, dst.data_ptr() + 3, n, 0) == n
+    plan = tp.last_plan()
+    assert plan.count("shift W=4") == 2, plan
+    assert torch.equal(dst[3:3 + n], src[1:1 + n])
+    assert int(dst[:3].sum()) == 0 and int(dst[3 + n:].sum()) == 0
+    dst.zero_()
+    try:
+        tp.set_override("shift", 0)
+        assert tp.pack(src.data_ptr() + 1, 1, h, dst.data_ptr() + 3, n, 0) == n
+    finally:
+        tp.set_override("shift", 1)
     plan = tp.last_plan()
     assert plan.count("tile") >= 2 and "W=1 " in plan, plan
     assert torch.equal(dst[3:3 + n], src[1:1 + n])

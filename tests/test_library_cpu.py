@@ -323,9 +323,10 @@ def test_emulated_shifted_copy_for_unlike_alignment():
             assert res["plan"].startswith("shift W=4 "), res["plan"]
     # every relative misalignment of the two sides, 3D, ragged run, several tiles
     t = hvector(3, 1, 7 * 5003, hvector(7, 1, 5003, contiguous(4099, BYTE)))
-    for ts in range(4):
-        for ps in range(4):
-            assert "shift" in _emulate_roundtrip(t, 1, typed_shift=ts, packed_shift=ps, position=1)["plan"]
+    for ts in range(8):
+        for ps in (0, 1, 2, 3, 5, 7):
+            assert "shift W=4" in _emulate_roundtrip(t, 1, typed_shift=ts, packed_shift=ps, position=1)["plan"]
+    assert "shift W=4" in _emulate_roundtrip(t, 1, typed_shift=1, max_word=8)["plan"]
     # aligned alike on both sides but at an odd address: still the shifted copy (4-byte words)
     assert "shift" in _emulate_roundtrip(contiguous(3000, BYTE), 1, typed_shift=1, packed_shift=1)["plan"]
     # short runs and 4-byte-aligned data keep the plain tile kernel; the override switches it off
