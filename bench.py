@@ -325,6 +325,40 @@ def extras(W, tp, torch, np, dev, stream):
     res["copy_64MiB_odd_addresses_bytewise"] = {"us": round(us, 2), "gbs": round(2 * odd / us / 1e3, 1)}
     del srcs, dsts
 
+    # the runtime's own 2D copy (the DMA-engine route the paper lists as future work, Sec. 8) on the
+    # same 2D shape as a sweep point: 64 MiB in 128-byte runs at 512-byte pitch, against this library
+    try:
+        import ctypes
+        hip = ctypes.CDLL(os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so"))
+        hip.hipMemcpy2DAsync.argtypes = [ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_size_t,
+                                         ctypes.c_size_t, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
+        hip.hipMemcpy2DAsync.restype = ctypes.c_int
+        rows2d, width2d, pitch2d = 1 << 19, 128, 512
+        src2d = [torch.empty(rows2d * pitch2d, dtype=torch.uint8, device=dev).fill_(i + 1) for i in range(4)]
+        dst2d = [torch.empty(rows2d * width2d, dtype=torch.uint8, device=dev) for _ in range(4)]
+        D2D = 3  # hipMemcpyDeviceToDevice
+
+        def dma2d():
+            j = k[0] % 4
+            rc = hip.hipMemcpy2DAsync(dst2d[j].data_ptr(), width2d, src2d[j].data_ptr(), pitch2d, width2d, rows2d, D2D,
+                                      stream.cuda_stream)
+            assert rc == 0, rc
+            k[0] += 1
+        us_dma = timed(dma2d, n=12)
+        t2d = tp.type_from_recipe(W.vector(rows2d, width2d, pitch2d, W.BYTE))
+
+        def ours2d():
+            j = k[0] % 4
+            tp.pack_async(src2d[j], 1, t2d, dst2d[j], rows2d * width2d, 0, stream)
+            k[0] += 1
+        us_ours = timed(ours2d, n=12)
+        same = bool(torch.equal(dst2d[0], src2d[0].view(rows2d, pitch2d)[:, :width2d].reshape(-1)))
+        res["pack_2d_64MiB_128B_runs_vs_hipMemcpy2DAsync"] = {
+            "hipMemcpy2DAsync_us": round(us_dma, 1), "tp_pack_us": round(us_ours, 1), "outputs_equal": same}
+        del src2d, dst2d
+    except Exception as e:  # a comparison point only
+        res["pack_2d_64MiB_128B_runs_vs_hipMemcpy2DAsync"] = f"not measured: {e}"
+
     # synchronous-call latency (launch + kernel + synchronize, the paper's timed region) on the small 2D vector
     c1 = W.configs.cfg1()
     buf = torch.zeros(c1["buffer_bytes"], dtype=torch.uint8, device=dev)
