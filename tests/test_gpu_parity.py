@@ -93,6 +93,52 @@ def test_random_small_types(dev):
         done += 1
 
 
+def _medium_recipe(rng):
+    """A non-overlapping nested type of up to a few MiB: a run of 1..6000 bytes (BYTE, INT16, FLOAT or
+    DOUBLE elements) under 1-3 levels of vector / hvector / subarray whose strides clear the child's extent."""
+    elem = rng.choice(("BYTE", "BYTE", "INT16", "FLOAT", "DOUBLE"))
+    esz = py.NAMED_SIZE[elem]
+    run_elems = max(1, rng.choice((1, 2, 3, 5, 8, 24, 61, 64, 100, 257, 1000, 6000)) // esz)
+    t = contiguous(run_elems, named(elem))
+    ext = run_elems * esz
+    budget = 4 << 20
+    for _ in range(rng.randint(1, 3)):
+        count = rng.choice((1, 2, 3, 7, 16, 33, 64, 200))
+        count = max(1, min(count, budget // max(1, cc.size(t))))
+        kind = rng.choice(("hvector", "vector", "subarray"))
+        if kind == "hvector":
+            stride = ext + rng.choice((0, 1, 3, 8, 16, 100, 4096))
+            t = hvector(count, 1, stride, t)
+        elif kind == "vector":
+            bl = rng.choice((1, 2, 3))
+            t = vector(count, bl, bl + rng.choice((0, 1, 2, 5)), t)
+        else:
+            size = count + rng.choice((0, 1, 5))
+            t = subarray((size, 3), (count, rng.choice((1, 2, 3))), (rng.randint(0, size - count), 0),
+                         rng.choice(("C", "F")), t)
+        ext = cc.extent(t)
+        budget = max(1, budget)
+    return t
+
+
+def test_random_medium_types(dev):
+    # seeded fuzz over shapes far larger than the CPU emulation can afford: every kernel variant,
+    # odd alignments, several objects, pack and unpack, against the C oracle
+    rng = random.Random(777)
+    kinds = set()
+    for i in range(150):
+        t = _medium_recipe(rng)
+        incount = rng.choice((1, 1, 2, 3))
+        if cc.size(t) * incount > (8 << 20) or cc.extent(t) * incount > (256 << 20):
+            continue
+        say("medium type", i, "size", cc.size(t), "extent", cc.extent(t), "incount", incount)
+        roundtrip(t, incount, dev, typed_shift=rng.choice((0, 0, 1, 2, 3, 4, 8, 16)),
+                  packed_shift=rng.choice((0, 0, 1, 2, 3, 4, 8)), position=rng.choice((0, 0, 1, 5, 16)), seed=i)
+        kinds.update(line.split(" ux=")[0] for line in tp.last_plan().splitlines())
+    say("variants seen:", sorted(kinds))
+    assert {"tile W=1", "tile W=4", "tile W=16", "shift W=4"} <= kinds
+
+
 @pytest.mark.parametrize("a0", [1, 2, 3, 4, 8, 16, 24, 48, 64, 200, 512, 1040, 4048, 4100, 4112, 20000])
 def test_tile_shapes_and_ragged_tails(dev, a0):
     say("tile shapes a0", a0)
