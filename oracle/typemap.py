@@ -15,6 +15,13 @@ here, so it can be compared with the standard by eye.  Pure Python loops:
 meant for types with up to ~1e6 blocks.  `oracle/typemap_c.py` wraps the same
 recursion written in C for the full-size workloads.
 
+What pins it (tests/test_oracle_pins.py, tests/test_oracle_mutations.py): the paper prints no
+expected bytes, type maps or IR in its text (its figures are not part of it), so nothing here is
+pinned by a value the paper states.  The pins are hand-enumerated type maps (tests/golden), closed
+forms of the MPI definitions, numpy slicing / reshape / as_strided as independent readings, the
+paper's lists of equivalent constructions (Sec. 2), and invariants; planted mistakes in every
+constructor rule are shown to trip them.
+
 Readings where the paper is silent (kept identical in the C twin):
   * extent = ub - lb exactly, no alignment padding;
   * a subarray has lb = 0 and ub = extent(old) * prod(sizes) whatever it selects;
@@ -40,7 +47,10 @@ NAMED_SIZE = {
 
 # ----------------------------------------------------------------- placements
 def placements(t):
-    """Displacements at which constructor `t` places copies of its oldtype, in type-map order."""
+    """Displacements at which constructor `t` places copies of its oldtype, in type-map order.
+
+    The constructor list of the paper's Sec. 2 (MPI-3.1 Sec. 4.1.2 for contiguous / vector /
+    hvector, Sec. 4.1.3 for subarray), one case each."""
     kind = t[0]
     old = t[-1]
     ex = extent(old)
@@ -118,7 +128,8 @@ def size(t) -> int:
 
 # ------------------------------------------------------------------- type map
 def type_map(t, d: int = 0):
-    """Yield the (displacement, length) blocks of recipe `t` placed at displacement d."""
+    """Yield the (displacement, length) blocks of recipe `t` placed at displacement d: the MPI
+    type map (MPI-3.1 Sec. 4.1), which Sec. 2 of the paper takes as the meaning of a datatype."""
     if t[0] == "named":
         yield (d, NAMED_SIZE[t[1]])
         return
@@ -144,7 +155,7 @@ def has_overlap(t, incount: int = 1) -> bool:
 
 # ---------------------------------------------------------------- pack/unpack
 def pack(inbuf: np.ndarray, origin: int, incount: int, t, outbuf: np.ndarray, position: int) -> int:
-    """MPI_Pack: copy `incount` objects of type `t` whose origin is inbuf[origin]
+    """MPI_Pack (paper Sec. 6.2: the typed buffer is sent into a contiguous one): copy `incount` objects of type `t` whose origin is inbuf[origin]
     to outbuf[position:], returning the new position.  Raises if it would not fit."""
     ex = extent(t)
     if position + incount * size(t) > outbuf.size:
