@@ -218,35 +218,38 @@ def _stream(stream) -> int:
     return stream.cuda_stream
 
 
-def _transfer(fn_name, first, mid, position, stream):
+def _pack_call(fn_name, inbuf, incount, t, outbuf, outsize, position, stream):
     pos = ctypes.c_int64(position)
-    fn = getattr(lib(), fn_name)
-    if "unpack" in fn_name:
-        inbuf, insize, outbuf, outcount, t = first, mid[0], mid[1], mid[2], mid[3]
-        rc = fn(_ptr(inbuf), insize, ctypes.byref(pos), _ptr(outbuf), outcount, t, _stream(stream))
-    else:
-        inbuf, incount, t, outbuf, outsize = first, mid[0], mid[1], mid[2], mid[3]
-        rc = fn(_ptr(inbuf), incount, t, _ptr(outbuf), outsize, ctypes.byref(pos), _stream(stream))
+    rc = getattr(lib(), fn_name)(_ptr(inbuf), incount, t, _ptr(outbuf), outsize, ctypes.byref(pos), _stream(stream))
+    _check(rc, fn_name)
+    return pos.value
+
+
+def _unpack_call(fn_name, inbuf, insize, position, outbuf, outcount, t, stream):
+    pos = ctypes.c_int64(position)
+    rc = getattr(lib(), fn_name)(_ptr(inbuf), insize, ctypes.byref(pos), _ptr(outbuf), outcount, t, _stream(stream))
     _check(rc, fn_name)
     return pos.value
 
 
 def pack(inbuf, incount: int, t: int, outbuf, outsize: int, position: int, stream=None) -> int:
     """tp_pack; returns the new position."""
-    return _transfer("tp_pack", inbuf, (incount, t, outbuf, outsize), position, stream)
+    return _pack_call("tp_pack", inbuf, incount, t, outbuf, outsize, position, stream)
 
 
 def pack_async(inbuf, incount: int, t: int, outbuf, outsize: int, position: int, stream=None) -> int:
-    return _transfer("tp_pack_async", inbuf, (incount, t, outbuf, outsize), position, stream)
+    """tp_pack_async (enqueue only); returns the new position."""
+    return _pack_call("tp_pack_async", inbuf, incount, t, outbuf, outsize, position, stream)
 
 
 def unpack(inbuf, insize: int, position: int, outbuf, outcount: int, t: int, stream=None) -> int:
     """tp_unpack; returns the new position."""
-    return _transfer("tp_unpack", inbuf, (insize, outbuf, outcount, t), position, stream)
+    return _unpack_call("tp_unpack", inbuf, insize, position, outbuf, outcount, t, stream)
 
 
 def unpack_async(inbuf, insize: int, position: int, outbuf, outcount: int, t: int, stream=None) -> int:
-    return _transfer("tp_unpack_async", inbuf, (insize, outbuf, outcount, t), position, stream)
+    """tp_unpack_async (enqueue only); returns the new position."""
+    return _unpack_call("tp_unpack_async", inbuf, insize, position, outbuf, outcount, t, stream)
 
 
 class Batch:
