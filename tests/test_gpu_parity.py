@@ -169,6 +169,18 @@ def test_shifted_copy_for_unlike_alignment(dev, run):
         tp.set_override("shift", 1)
 
 
+def test_sixteen_dimensions(dev):
+    # 15 nested two-element levels and two objects: 16 row dimensions, the most a launch carries
+    say("sixteen dimensions")
+    t = contiguous(3, BYTE)
+    stride = 4
+    for _ in range(15):
+        t = hvector(2, 1, stride, t)
+        stride = 2 * stride + 1
+    roundtrip(t, 2, dev, typed_shift=1, seed=16)
+    assert "nrd=16" in tp.last_plan()
+
+
 def test_word_widths_forced(dev):
     t = vector(300, 64, 96, BYTE)
     try:

@@ -456,3 +456,34 @@ def test_handle_table_and_commit_are_thread_safe():
     [t.join() for t in threads]
     assert not errors, errors[:1]
     tp.type_free(shared)
+
+
+def _deep_type(levels, run=3):
+    """`levels` nested 2-element hvectors whose strides never let two levels merge."""
+    t = contiguous(run, BYTE)
+    stride = run + 1
+    for _ in range(levels):
+        t = hvector(2, 1, stride, t)
+        stride = 2 * stride + 1
+    return t
+
+
+def test_many_dimensions():
+    # 14 row dimensions plus the run: the looped (not unrolled) row decomposition, all 2^14 rows
+    t = _deep_type(14)
+    h = tp.type_from_recipe(t)
+    start, counts, strides = tp.type_get_strided_block(h)
+    assert counts == [3] + [2] * 14 and len(set(strides)) == 15
+    res = _emulate_roundtrip(t, 1, typed_shift=1)
+    assert "nrd=14" in res["plan"]
+    # with two objects the count adds a 15th row dimension; 16 dimensions is the limit
+    assert "nrd=15" in _emulate_roundtrip(_deep_type(14), 2)["plan"]
+    assert tp.type_get_strided_block(tp.type_from_recipe(_deep_type(15)))[1] == [3] + [2] * 15
+    assert "nrd=16" in _emulate_roundtrip(_deep_type(15), 2)["plan"]   # every row-dimension slot in use
+    too_deep = tp.type_from_recipe(_deep_type(16), commit=False)
+    with pytest.raises(tp.TpError) as e:
+        tp.type_commit(too_deep)
+    assert e.value.code == tp.TP_ERR_RANGE
+    with pytest.raises(tp.TpError) as e:      # a type whose commit failed stays unusable
+        tp.type_get_strided_block(too_deep)
+    assert e.value.code == tp.TP_ERR_TYPE
