@@ -712,3 +712,39 @@ def test_run_longer_than_one_launch_takes(dev):
     assert plan.count("tile") >= 2 and "W=1 " in plan, plan
     assert torch.equal(dst[3:3 + n], src[1:1 + n])
     assert int(dst[:3].sum()) == 0 and int(dst[3 + n:].sum()) == 0
+
+
+def test_two_threads_two_streams(dev):
+    # pack/unpack calls from different host threads on different streams may overlap
+    import threading
+
+    t = hvector(64, 1, 9000, vector(33, 24, 40, FLOAT))
+    h = tp.type_from_recipe(t)
+    size, ex = tp.type_size(h), tp.type_get_extent(h)[1]
+    errors = []
+
+    def worker(k):
+        try:
+            stream = torch.cuda.Stream()
+            src_h = W.random_bytes(900 + k, ex)
+            expect = np.zeros(size, np.uint8)
+            cc.pack(src_h, 0, 1, t, expect, 0)
+            with torch.cuda.stream(stream):
+                src = to_dev(src_h, dev)
+                out = torch.zeros(size, dtype=torch.uint8, device=dev)
+                back = torch.full((ex,), 0xA5, dtype=torch.uint8, device=dev)
+                for _ in range(50):
+                    assert tp.pack(src, 1, h, out, size, 0, stream) == size
+                    assert tp.unpack(out, size, 0, back, 1, h, stream) == size
+                got, got_back = out.cpu().numpy(), back.cpu().numpy()
+            want = np.full(ex, 0xA5, np.uint8)
+            cc.unpack(expect, 0, want, 0, 1, t)
+            assert np.array_equal(got, expect) and np.array_equal(got_back, want)
+        except Exception as e:  # noqa: BLE001
+            errors.append(e)
+
+    say("two threads, two streams")
+    threads = [threading.Thread(target=worker, args=(k,)) for k in range(2)]
+    [th.start() for th in threads]
+    [th.join() for th in threads]
+    assert not errors, errors[:1]
