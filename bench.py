@@ -20,6 +20,7 @@ from __future__ import annotations
 import argparse
 import json
 import os
+import subprocess
 import sys
 import time
 
@@ -374,7 +375,6 @@ def extras(W, tp, torch, np, dev, stream):
 
     # commit time per type: the plain-C program timing create and commit through the C ABI,
     # trimean of 30000 cycles per type (the statistic of the paper's Sec. 6.1)
-    import subprocess
     import tempfile
 
     # measured performance model (paper Sec. 4 / 6.3): measure the system, keep the table, and ask it
@@ -424,6 +424,59 @@ def extras(W, tp, torch, np, dev, stream):
             res["canonicalize_us_per_type"] = f"commit_timing failed: {e}"
     else:
         res["canonicalize_us_per_type"] = "commit_timing not built"
+    res["resource_cache"] = resource_cache_timing(W, tp, torch, dev, stream)
+    return res
+
+
+def resource_cache_timing(W, tp, torch, dev, stream):
+    """Paper Sec. 5: what a repeated request for a buffer, stream or event costs from the library's
+    cache against what the runtime takes to create one, and what a pack call saves on buffers the
+    cache knows (no memory-residency query)."""
+    res = {}
+    exe = os.path.join(ROOT, "paper_2012_14363_amd", "resource_timing")
+    if os.path.exists(exe):
+        try:
+            rows = json.loads(subprocess.run([exe, "500000", "16"], capture_output=True, text=True, timeout=120,
+                                             check=True).stdout)
+            res["per_kind"] = [{"kind": r["kind"], "create_us": round(r["create_median_ns"] / 1e3, 2),
+                                "cached_acquire_release_ns": r["cached_pair_ns"]} for r in rows]
+        except Exception as e:  # reported, never fatal for the benchmark line
+            res["per_kind"] = f"resource_timing failed: {e}"
+    else:
+        res["per_kind"] = "resource_timing not built"
+
+    # host time of an enqueue-only pack call: both buffers leased from the cache vs. both torch's
+    h = tp.type_from_recipe(W.vector(64, 8, 512, W.BYTE))
+    size, ex = tp.type_size(h), tp.type_get_extent(h)[1]
+    calls = 20000
+
+    def per_call_us(src, dst):
+        for _ in range(200):
+            tp.pack_async(src, 1, h, dst, size, 0, stream)
+        stream.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(calls):
+            tp.pack_async(src, 1, h, dst, size, 0, stream)
+        dt = time.perf_counter() - t0
+        stream.synchronize()
+        return dt / calls * 1e6
+
+    src_t = torch.zeros(ex, dtype=torch.uint8, device=dev)
+    dst_t = torch.zeros(size, dtype=torch.uint8, device=dev)
+    src_l = tp.resource_acquire(tp.TP_RES_DEVICE, ex)
+    dst_l = tp.resource_acquire(tp.TP_RES_DEVICE, size)
+    try:
+        res["pack_async_host_us_per_call"] = {
+            "queried_buffers": round(per_call_us(src_t.data_ptr(), dst_t.data_ptr()), 2),
+            "leased_buffers": round(per_call_us(src_l, dst_l), 2),
+            "calls": calls,
+            "note": "512-byte object; the loop is Python + ctypes, equal on both sides; the difference is the "
+                    "two residency queries per call",
+        }
+    finally:
+        tp.resource_release(tp.TP_RES_DEVICE, src_l)
+        tp.resource_release(tp.TP_RES_DEVICE, dst_l)
+        tp.resource_trim()
     return res
 
 

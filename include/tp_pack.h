@@ -176,10 +176,13 @@ int tp_unpack_batch_async(int n, const void *inbuf, int64_t insize, int64_t *pos
  *     rank to measure and are therefore inputs (seconds; 0 if unknown).  *method receives the
  *     fastest of TP_METHOD_DEVICE / ONESHOT / STAGED; times (may be NULL) the three totals.
  * tp_pack_host: tp_pack whose outbuf is pinned host memory, by the method asked for:
- *     TP_METHOD_ONESHOT, TP_METHOD_STAGED (needs `staging`, device memory of at least incount*size
- *     bytes, caller-owned), or TP_METHOD_AUTO (staged if the model predicts gpu_pack + d2h <
- *     host_pack and staging is large enough, else one-shot).  Synchronizes.  *method_used (may be
- *     NULL) reports the choice.  tp_unpack_host is the mirror (host inbuf -> device typed buffer).
+ *     TP_METHOD_ONESHOT, TP_METHOD_STAGED (through `staging`, caller-owned device memory of
+ *     staging_size >= incount*size bytes; with staging NULL the library leases a device buffer
+ *     from its resource cache for the duration of the call, see below), or TP_METHOD_AUTO
+ *     (staged if the model predicts gpu_pack + d2h < host_pack, else one-shot).  A non-NULL
+ *     staging that is too small is TP_ERR_ARG for STAGED and means one-shot for AUTO.
+ *     Synchronizes.  *method_used (may be NULL) reports the choice.  tp_unpack_host is the mirror
+ *     (host inbuf -> device typed buffer).
  */
 typedef struct tp_model_times {
     double gpu_pack, gpu_unpack, host_pack, host_unpack, d2h, h2d;
@@ -199,6 +202,46 @@ int tp_pack_host(const void *inbuf, int incount, tp_type t, void *host_outbuf, i
                  void *staging, int64_t staging_size, int method, void *hip_stream, int *method_used);
 int tp_unpack_host(const void *host_inbuf, int64_t insize, int64_t *position, void *outbuf, int outcount, tp_type t,
                    void *staging, int64_t staging_size, int method, void *hip_stream, int *method_used);
+
+/* ---- resource cache (Sec. 5) ------------------------------------------------------------------
+ * A send/receive layer built on this library needs, per message, an intermediate buffer (device
+ * or pinned host), often a stream and an event.  Creating them costs the runtime microseconds to
+ * milliseconds; Sec. 5 serves repeated requests from a cache instead.  Resources are leased and
+ * given back; a released resource stays alive and serves the next request of its kind on the
+ * same device (buffers: of the same size class - capacities are rounded up to a quarter step of
+ * a power of two, 4 KiB at least).  All calls are thread-safe.
+ *
+ * tp_resource_acquire: kind TP_RES_DEVICE (device memory), TP_RES_PINNED (page-locked host
+ *     memory mapped into the device's address space, usable as the contiguous side of any
+ *     pack/unpack call), TP_RES_STREAM (a hipStream_t, non-blocking, default priority) or
+ *     TP_RES_EVENT (a hipEvent_t without timing).  `bytes` >= 0 is the least capacity of a buffer
+ *     and ignored otherwise.  *handle receives the buffer address / stream / event, created on the
+ *     calling thread's current device.  Buffer contents are whatever the last holder left.
+ *     TP_ERR_ARG for a bad kind, negative bytes or NULL handle; TP_ERR_OTHER if the runtime cannot
+ *     create the resource even after idle resources were freed.
+ * tp_resource_release: gives a lease back.  The caller must first have waited for all device work
+ *     that uses it: the next holder may get it at once.  TP_ERR_ARG if `handle` is not a current
+ *     lease of that kind (never leased, or released already).
+ * tp_resource_trim: destroys every idle resource; *bytes_freed (may be NULL) = buffer bytes.
+ * tp_resource_stats: counters of one kind since the process started.
+ * Pointers into a leased buffer are recognised by pack/unpack without the per-call
+ * memory-residency query.  Nothing is freed at process exit.
+ */
+#define TP_RES_DEVICE 0
+#define TP_RES_PINNED 1
+#define TP_RES_STREAM 2
+#define TP_RES_EVENT 3
+
+typedef struct tp_resource_counts {
+    int64_t hits, misses;              /* acquires served from the cache / by the runtime */
+    int64_t idle, leased;              /* resources alive now */
+    int64_t idle_bytes, leased_bytes;  /* buffer capacities (0 for streams and events) */
+} tp_resource_counts;
+
+int tp_resource_acquire(int kind, int64_t bytes, void **handle);
+int tp_resource_release(int kind, void *handle);
+int tp_resource_trim(int64_t *bytes_freed);
+int tp_resource_stats(int kind, tp_resource_counts *out);
 
 /* ---- introspection for tests and ablations ------------------------------------------------------
  * tp_type_get_strided_block: the canonical form of a committed type (Sec. 3.3): *ndims dimensions,

@@ -33,11 +33,21 @@ EXPORTS = (
     "tp_pack_batch", "tp_unpack_batch", "tp_pack_batch_async", "tp_unpack_batch_async",
     "tp_model_measure", "tp_model_save", "tp_model_load", "tp_model_query", "tp_model_select",
     "tp_pack_host", "tp_unpack_host",
+    "tp_resource_acquire", "tp_resource_release", "tp_resource_trim", "tp_resource_stats",
     "tp_type_get_strided_block", "tp_set_override", "tp_last_plan", "tp_error_string",
 )
 
 
 TP_METHOD_AUTO, TP_METHOD_DEVICE, TP_METHOD_ONESHOT, TP_METHOD_STAGED = -1, 0, 1, 2
+TP_RES_DEVICE, TP_RES_PINNED, TP_RES_STREAM, TP_RES_EVENT = 0, 1, 2, 3
+
+
+class ResourceCounts(ctypes.Structure):
+    """tp_resource_counts"""
+    _fields_ = [(n, ctypes.c_int64) for n in ("hits", "misses", "idle", "leased", "idle_bytes", "leased_bytes")]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
 
 
 class ModelTimes(ctypes.Structure):
@@ -102,6 +112,10 @@ def lib() -> ctypes.CDLL:
                                 ctypes.POINTER(ctypes.c_double)],
             "tp_pack_host": [vp, ctypes.c_int, i32, vp, i64, pi64, vp, i64, ctypes.c_int, vp, pint],
             "tp_unpack_host": [vp, i64, pi64, vp, ctypes.c_int, i32, vp, i64, ctypes.c_int, vp, pint],
+            "tp_resource_acquire": [ctypes.c_int, i64, pvp],
+            "tp_resource_release": [ctypes.c_int, vp],
+            "tp_resource_trim": [pi64],
+            "tp_resource_stats": [ctypes.c_int, ctypes.POINTER(ResourceCounts)],
             "tp_type_get_strided_block": [i32, pint, pi64, pi64, pi64],
             "tp_set_override": [ctypes.c_char_p, ctypes.c_char_p],
         }
@@ -342,6 +356,31 @@ def unpack_host(host_inbuf, insize, position, outbuf, outcount, t, staging=None,
                               ctypes.byref(used))
     _check(rc, "tp_unpack_host")
     return pos.value, used.value
+
+
+# ------------------------------------------------------------------ resource cache
+def resource_acquire(kind: int, nbytes: int = 0) -> int:
+    """tp_resource_acquire; returns the handle (buffer address, hipStream_t or hipEvent_t) as an int."""
+    h = ctypes.c_void_p()
+    _check(lib().tp_resource_acquire(kind, nbytes, ctypes.byref(h)), "tp_resource_acquire")
+    return h.value
+
+
+def resource_release(kind: int, handle: int) -> None:
+    _check(lib().tp_resource_release(kind, handle), "tp_resource_release")
+
+
+def resource_trim() -> int:
+    """tp_resource_trim; returns the buffer bytes freed."""
+    freed = ctypes.c_int64()
+    _check(lib().tp_resource_trim(ctypes.byref(freed)), "tp_resource_trim")
+    return freed.value
+
+
+def resource_stats(kind: int) -> dict:
+    c = ResourceCounts()
+    _check(lib().tp_resource_stats(kind, ctypes.byref(c)), "tp_resource_stats")
+    return c.as_dict()
 
 
 # ------------------------------------------------------------------ recipes -> handles

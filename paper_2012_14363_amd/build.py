@@ -10,7 +10,8 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.path.join(PKG_DIR, "libtp_pack.so")
 
-SOURCES = ["api.cpp", "model_api.cpp", "model.cpp", "type_tree.cpp", "canon.cpp", "plan.cpp", "kernels.hip"]
+SOURCES = ["api.cpp", "model_api.cpp", "model.cpp", "resource_api.cpp", "resource_cache.cpp", "type_tree.cpp",
+           "canon.cpp", "plan.cpp", "kernels.hip"]
 
 
 def hipcc() -> str:
@@ -36,6 +37,7 @@ def build(verbose: bool = False) -> str:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
     build_commit_timing()
+    build_resource_timing()
     return LIB_PATH
 
 
@@ -49,6 +51,19 @@ def build_commit_timing() -> str:
         "-L", PKG_DIR, "-ltp_pack", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath-link," + "/opt/rocm/lib", "-o", TIMING_EXE,
     ])
     return TIMING_EXE
+
+
+RESOURCE_TIMING_EXE = os.path.join(PKG_DIR, "resource_timing")
+
+
+def build_resource_timing() -> str:
+    """The plain-C resource-cache microbenchmark, linked against the library just built."""
+    subprocess.check_call([
+        "gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-I", INCLUDE, os.path.join(CSRC, "resource_timing.c"),
+        "-L", PKG_DIR, "-ltp_pack", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath-link," + "/opt/rocm/lib", "-o",
+        RESOURCE_TIMING_EXE,
+    ])
+    return RESOURCE_TIMING_EXE
 
 
 if __name__ == "__main__":

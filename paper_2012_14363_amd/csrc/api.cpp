@@ -14,6 +14,7 @@
 #include "canon.hpp"
 #include "kernels.hpp"
 #include "plan.hpp"
+#include "resource_cache.hpp"
 #include "status.hpp"
 #include "type_tree.hpp"
 
@@ -77,6 +78,11 @@ int resolve_pointer(const void* ptr, bool allow_host, const char** device_view) 
         *device_view = static_cast<const char*>(ptr);
         return kSuccess;
     }
+    // buffers leased from the library's own cache are known without asking the runtime
+    int kind = 0;
+    int64_t room = 0;
+    if (library_resources().find_leased(ptr, &kind, device_view, &room))
+        return kind == kResDevice || allow_host ? kSuccess : kErrBuffer;
     hipPointerAttribute_t attr;
     std::memset(&attr, 0, sizeof attr);
     const hipError_t e = hipPointerGetAttributes(&attr, ptr);

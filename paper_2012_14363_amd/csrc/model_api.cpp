@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "model.hpp"
+#include "resource_cache.hpp"
 #include "status.hpp"
 
 namespace {
@@ -67,6 +68,35 @@ int model_key(tp_type t, int count, int64_t* bytes, int64_t* block) {
     *block = nd > 1 ? counts[0] : std::max<int64_t>(size, 1);
     return kSuccess;
 }
+
+// The device buffer of a staged transfer: the caller's, or with none given a lease from the
+// library's resource cache that ends with the call (which has synchronized by then).
+struct Staging {
+    void* ptr = nullptr;
+    int64_t size = 0;
+    bool leased = false;
+    hipStream_t stream = nullptr;
+    bool drained = false;  // set once the stream has been waited for after the last use of ptr
+    int take(void* callers, int64_t callers_size, int64_t bytes, hipStream_t s) {
+        stream = s;
+        if (callers) {
+            ptr = callers;
+            size = callers_size;
+            return kSuccess;
+        }
+        const int rc = library_resources().acquire(kResDevice, bytes, &ptr);
+        if (rc != kSuccess) return rc;
+        size = bytes;
+        leased = true;
+        return kSuccess;
+    }
+    ~Staging() {
+        if (!leased) return;
+        // an error path may leave a copy or kernel in flight: the next holder must not see it
+        if (!drained) (void)hipStreamSynchronize(stream);
+        (void)library_resources().release(kResDevice, ptr);
+    }
+};
 
 }  // namespace
 
@@ -202,7 +232,7 @@ int tp_pack_host(const void* inbuf, int incount, tp_type t, void* host_outbuf, i
     int64_t bytes;
     int rc = tp_pack_size(incount, t, &bytes);
     if (rc != kSuccess) return rc;
-    const bool can_stage = staging != nullptr && staging_size >= bytes;
+    const bool can_stage = staging == nullptr || staging_size >= bytes;
     if (method == TP_METHOD_STAGED && !can_stage) return kErrArg;
     if (method == TP_METHOD_AUTO) {
         method = TP_METHOD_ONESHOT;
@@ -216,15 +246,19 @@ int tp_pack_host(const void* inbuf, int incount, tp_type t, void* host_outbuf, i
         if (*position < 0 || outsize < 0) return kErrArg;
         if (bytes > outsize - *position) return kErrTruncate;
         if (bytes > 0 && !host_outbuf) return kErrBuffer;
-        int64_t staged = 0;
-        rc = tp_pack_async(inbuf, incount, t, staging, staging_size, &staged, hip_stream);
-        if (rc != kSuccess) return rc;
         hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+        Staging stage;
+        rc = stage.take(staging, staging_size, bytes, stream);
+        if (rc != kSuccess) return rc;
+        int64_t staged = 0;
+        rc = tp_pack_async(inbuf, incount, t, stage.ptr, stage.size, &staged, hip_stream);
+        if (rc != kSuccess) return rc;
         if (bytes > 0 &&
-            hipMemcpyAsync(static_cast<char*>(host_outbuf) + *position, staging, static_cast<size_t>(bytes),
+            hipMemcpyAsync(static_cast<char*>(host_outbuf) + *position, stage.ptr, static_cast<size_t>(bytes),
                            hipMemcpyDeviceToHost, stream) != hipSuccess)
             return kErrOther;
         if (hipStreamSynchronize(stream) != hipSuccess) return kErrOther;
+        stage.drained = true;
         *position += bytes;
     }
     if (rc == kSuccess && method_used) *method_used = method;
@@ -238,7 +272,7 @@ int tp_unpack_host(const void* host_inbuf, int64_t insize, int64_t* position, vo
     int64_t bytes;
     int rc = tp_pack_size(outcount, t, &bytes);
     if (rc != kSuccess) return rc;
-    const bool can_stage = staging != nullptr && staging_size >= bytes;
+    const bool can_stage = staging == nullptr || staging_size >= bytes;
     if (method == TP_METHOD_STAGED && !can_stage) return kErrArg;
     if (method == TP_METHOD_AUTO) {
         method = TP_METHOD_ONESHOT;
@@ -253,13 +287,17 @@ int tp_unpack_host(const void* host_inbuf, int64_t insize, int64_t* position, vo
         if (bytes > insize - *position) return kErrTruncate;
         if (bytes > 0 && !host_inbuf) return kErrBuffer;
         hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+        Staging stage;
+        rc = stage.take(staging, staging_size, bytes, stream);
+        if (rc != kSuccess) return rc;
         if (bytes > 0 &&
-            hipMemcpyAsync(staging, static_cast<const char*>(host_inbuf) + *position, static_cast<size_t>(bytes),
+            hipMemcpyAsync(stage.ptr, static_cast<const char*>(host_inbuf) + *position, static_cast<size_t>(bytes),
                            hipMemcpyHostToDevice, stream) != hipSuccess)
             return kErrOther;
         int64_t staged = 0;
-        rc = tp_unpack(staging, bytes, &staged, outbuf, outcount, t, hip_stream);
+        rc = tp_unpack(stage.ptr, bytes, &staged, outbuf, outcount, t, hip_stream);
         if (rc != kSuccess) return rc;
+        stage.drained = true;  // tp_unpack has waited for the copy and its kernels (none if bytes == 0)
         *position += bytes;
     }
     if (rc == kSuccess && method_used) *method_used = method;

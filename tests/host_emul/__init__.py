@@ -10,16 +10,17 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(os.path.dirname(_HERE))
 _CSRC = os.path.join(_ROOT, "paper_2012_14363_amd", "csrc")
 _LIB = os.path.join(_HERE, "libtp_emul.so")
-_SOURCES = [os.path.join(_HERE, "emul.cpp"), os.path.join(_CSRC, "plan.cpp")]
+_SOURCES = [os.path.join(_HERE, "emul.cpp"), os.path.join(_HERE, "cache_emul.cpp"), os.path.join(_CSRC, "plan.cpp"),
+            os.path.join(_CSRC, "resource_cache.cpp")]
 _lib = None
 
 
 def build(force=True):
-    deps = _SOURCES + [os.path.join(_CSRC, h) for h in ("plan.hpp", "tile_body.hpp", "fastdiv.hpp", "strided_block.hpp")]
+    deps = _SOURCES + [os.path.join(_CSRC, h) for h in ("plan.hpp", "tile_body.hpp", "fastdiv.hpp", "strided_block.hpp", "resource_cache.hpp")]
     stale = not os.path.exists(_LIB) or any(os.path.getmtime(d) > os.path.getmtime(_LIB) for d in deps)
     if force or stale:
         subprocess.check_call(["g++", "-O2", "-g", "-std=c++20", "-Wall", "-Wextra", "-Wno-unknown-pragmas", "-fPIC",
-                               "-shared", "-I", _CSRC, *_SOURCES, "-o", _LIB])
+                               "-shared", "-pthread", "-I", _CSRC, *_SOURCES, "-o", _LIB])
     return _LIB
 
 
@@ -38,8 +39,83 @@ def _load():
         L.emul_transfer_batch.restype = ctypes.c_int
         L.emul_fastdiv_mismatches.argtypes = [ctypes.c_uint32, i64, ctypes.c_uint64]
         L.emul_fastdiv_mismatches.restype = i64
+        L.cache_emul_new.restype = vp
+        L.cache_emul_delete.argtypes = [vp]
+        L.cache_emul_acquire.argtypes = [vp, ctypes.c_int, i64, ctypes.POINTER(vp)]
+        L.cache_emul_release.argtypes = [vp, ctypes.c_int, vp]
+        L.cache_emul_trim.argtypes = [vp]
+        L.cache_emul_trim.restype = i64
+        L.cache_emul_counts.argtypes = [vp, ctypes.c_int, p64]
+        L.cache_emul_find.argtypes = [vp, vp, pint, p64, p64]
+        L.cache_emul_capacity.argtypes = [i64]
+        L.cache_emul_capacity.restype = i64
+        L.cache_emul_backend.argtypes = [ctypes.c_int, p64]
+        L.cache_emul_hammer.argtypes = [vp, ctypes.c_int, ctypes.c_int]
+        L.cache_emul_hammer.restype = i64
         _lib = L
     return _lib
+
+
+COUNT_FIELDS = ("hits", "misses", "idle", "leased", "idle_bytes", "leased_bytes")
+
+
+class Cache:
+    """The library's ResourceCache over the host heap (cache_emul.cpp)."""
+
+    def __init__(self):
+        self._L = _load()
+        self._c = self._L.cache_emul_new()
+
+    def close(self):
+        if self._c:
+            self._L.cache_emul_delete(self._c)
+            self._c = None
+
+    def acquire(self, kind, nbytes):
+        """(status, handle address or None)"""
+        h = ctypes.c_void_p()
+        rc = self._L.cache_emul_acquire(self._c, kind, nbytes, ctypes.byref(h))
+        return rc, h.value
+
+    def release(self, kind, handle):
+        return self._L.cache_emul_release(self._c, kind, handle)
+
+    def trim(self):
+        return self._L.cache_emul_trim(self._c)
+
+    def counts(self, kind):
+        out = (ctypes.c_int64 * 6)()
+        self._L.cache_emul_counts(self._c, kind, out)
+        return dict(zip(COUNT_FIELDS, out))
+
+    def find(self, address):
+        """None, or (kind, gpu view minus address, bytes to the buffer's end)."""
+        kind, delta, room = ctypes.c_int(), ctypes.c_int64(), ctypes.c_int64()
+        if not self._L.cache_emul_find(self._c, address, ctypes.byref(kind), ctypes.byref(delta), ctypes.byref(room)):
+            return None
+        return kind.value, delta.value, room.value
+
+    def hammer(self, threads, rounds):
+        return self._L.cache_emul_hammer(self._c, threads, rounds)
+
+
+def cache_capacity(nbytes):
+    return _load().cache_emul_capacity(nbytes)
+
+
+def cache_backend(kind):
+    """Backend tallies: (created, destroyed) of `kind`, live buffer bytes of all kinds."""
+    out = (ctypes.c_int64 * 3)()
+    _load().cache_emul_backend(kind, out)
+    return tuple(out)
+
+
+def cache_fail_next(n):
+    _load().cache_emul_fail_next(n)
+
+
+def cache_set_device(d):
+    _load().cache_emul_set_device(d)
 
 
 def fastdiv_mismatches(small_limit, random_pairs, seed):

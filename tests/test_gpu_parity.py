@@ -659,6 +659,113 @@ def test_model_measure_and_host_delivery(dev, tmp_path):
     assert np.array_equal(host.numpy(), expect[4:])
 
 
+# ------------------------------------------------------------------ resource cache
+class _DeviceView:
+    """Zero-copy torch view of `n` bytes of device memory at `address` (owned elsewhere)."""
+
+    def __init__(self, address, n):
+        self.__cuda_array_interface__ = {"shape": (n,), "typestr": "|u1", "data": (address, False), "version": 2}
+
+
+def _host_view(address, n):
+    import ctypes
+    return np.ctypeslib.as_array((ctypes.c_uint8 * n).from_address(address))
+
+
+def test_resource_cache_buffers_serve_pack_and_unpack(dev):
+    t = hvector(40, 1, 5000, vector(19, 3, 7, named("INT16")))
+    h = tp.type_from_recipe(t)
+    size, ex = tp.type_size(h), tp.type_get_extent(h)[1]
+    src_h = W.random_bytes(501, ex)
+    src = to_dev(src_h, dev)
+    expect = np.zeros(size, np.uint8)
+    cc.pack(src_h, 0, 1, t, expect, 0)
+    before = {k: tp.resource_stats(k) for k in range(4)}
+
+    say("resource cache: device buffer as the packed side")
+    d = tp.resource_acquire(tp.TP_RES_DEVICE, size)
+    assert d % 256 == 0
+    assert tp.pack(src, 1, h, d + 2, size, 0) == size  # an odd offset inside the lease
+    got = torch.as_tensor(_DeviceView(d, size + 2), device=dev).cpu().numpy()
+    assert np.array_equal(got[2:], expect)
+
+    say("resource cache: pinned buffer as the packed side, both directions")
+    p = tp.resource_acquire(tp.TP_RES_PINNED, size)
+    host = _host_view(p, size)
+    host[:] = 0
+    assert tp.pack(src, 1, h, p, size, 0) == size
+    assert np.array_equal(host, expect)
+    back = torch.full((ex,), 0xA5, dtype=torch.uint8, device=dev)
+    assert tp.unpack(p, size, 0, back, 1, h) == size
+    want = np.full(ex, 0xA5, np.uint8)
+    cc.unpack(expect, 0, want, 0, 1, t)
+    assert np.array_equal(back.cpu().numpy(), want)
+    # a leased pinned buffer is still host memory: not acceptable as the typed side
+    with pytest.raises(tp.TpError) as e:
+        tp.pack(p, 1, tp.type_from_recipe(contiguous(16, BYTE)), d, size, 0)
+    assert e.value.code == tp.TP_ERR_BUFFER
+
+    say("resource cache: stream and event from the cache")
+    s = tp.resource_acquire(tp.TP_RES_STREAM)
+    ev = tp.resource_acquire(tp.TP_RES_EVENT)
+    out = torch.zeros(size, dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    assert tp.pack(src, 1, h, out, size, 0, s) == size  # synchronizes on s
+    assert np.array_equal(out.cpu().numpy(), expect)
+
+    say("resource cache: release, reuse, trim")
+    for kind, handle in ((tp.TP_RES_DEVICE, d), (tp.TP_RES_PINNED, p), (tp.TP_RES_STREAM, s), (tp.TP_RES_EVENT, ev)):
+        tp.resource_release(kind, handle)
+        with pytest.raises(tp.TpError) as e:
+            tp.resource_release(kind, handle)
+        assert e.value.code == tp.TP_ERR_ARG
+        again = tp.resource_acquire(kind, size)
+        assert again == handle
+        tp.resource_release(kind, again)
+        now = tp.resource_stats(kind)
+        assert now["misses"] - before[kind]["misses"] == 1 and now["hits"] - before[kind]["hits"] == 1
+        assert now["leased"] == before[kind]["leased"] and now["idle"] == before[kind]["idle"] + 1
+    idle = tp.resource_stats(tp.TP_RES_DEVICE)["idle_bytes"] + tp.resource_stats(tp.TP_RES_PINNED)["idle_bytes"]
+    assert tp.resource_trim() == idle and tp.resource_trim() == 0
+    assert all(tp.resource_stats(k)["idle"] == 0 for k in range(4))
+
+
+def test_staged_host_delivery_with_cached_staging(dev):
+    t = vector(3000, 40, 96, BYTE)
+    h = tp.type_from_recipe(t)
+    size, ex = tp.type_size(h), tp.type_get_extent(h)[1]
+    src_h = W.random_bytes(502, ex * 2)
+    src = to_dev(src_h, dev)
+    expect = np.full(size * 2 + 8, 0xEE, np.uint8)
+    cc.pack(src_h, 0, 2, t, expect, 8)
+    tp.resource_trim()
+    start = tp.resource_stats(tp.TP_RES_DEVICE)
+    for i in range(3):
+        say("staged delivery without a staging buffer, call", i)
+        host = torch.full((size * 2 + 8,), 0xEE, dtype=torch.uint8).pin_memory()
+        assert tp.pack_host(src, 2, h, host, size * 2 + 8, 8, None, 0, tp.TP_METHOD_STAGED) == \
+            (size * 2 + 8, tp.TP_METHOD_STAGED)
+        assert np.array_equal(host.numpy(), expect)
+        back = torch.full((ex * 2,), 0xA5, dtype=torch.uint8, device=dev)
+        assert tp.unpack_host(host, size * 2 + 8, 8, back, 2, h, None, 0, tp.TP_METHOD_STAGED) == \
+            (size * 2 + 8, tp.TP_METHOD_STAGED)
+        want = np.full(ex * 2, 0xA5, np.uint8)
+        cc.unpack(expect, 8, want, 0, 2, t)
+        assert np.array_equal(back.cpu().numpy(), want)
+    end = tp.resource_stats(tp.TP_RES_DEVICE)
+    # six staged transfers: one allocation, five served from the cache, nothing left leased
+    assert end["misses"] - start["misses"] == 1 and end["hits"] - start["hits"] == 5
+    assert end["leased"] == start["leased"] and end["idle"] == 1
+    # an error after the lease was taken (the typed buffer is pageable host memory) returns the lease
+    host = torch.zeros(size * 2, dtype=torch.uint8).pin_memory()
+    with pytest.raises(tp.TpError) as e:
+        tp.pack_host(torch.zeros(ex * 2, dtype=torch.uint8), 2, h, host, size * 2, 0, None, 0, tp.TP_METHOD_STAGED)
+    assert e.value.code == tp.TP_ERR_BUFFER
+    after = tp.resource_stats(tp.TP_RES_DEVICE)
+    assert after["leased"] == start["leased"] and after["hits"] == end["hits"] + 1
+    tp.resource_trim()
+
+
 # ------------------------------------------------------------------ maximum sizes
 def test_more_rows_than_one_launch_takes(dev):
     # 2^31 - 1 one-byte runs at stride 2: above the 2^30 rows a launch covers, so the planner splits
