@@ -360,6 +360,30 @@ def extras(W, tp, torch, np, dev, stream):
     except Exception as e:  # a comparison point only
         res["pack_2d_64MiB_128B_runs_vs_hipMemcpy2DAsync"] = f"not measured: {e}"
 
+    # an independent implementation of the narrowest sweep pattern (one byte per 512-byte row):
+    # PyTorch's strided copy kernels on views of the same buffers.  If the masked-write rate were a
+    # property of this library's kernel, another kernel would not share it.
+    rows1, pitch1 = 1 << 24, 512
+    typed1 = [torch.empty(rows1 * pitch1, dtype=torch.uint8, device=dev).fill_(7) for _ in range(2)]
+    packed1 = torch.empty(rows1, dtype=torch.uint8, device=dev).fill_(9)
+    t1 = tp.type_from_recipe(W.vector(rows1, 1, pitch1, W.BYTE))
+    ops = {
+        "torch_gather": lambda j: packed1.copy_(typed1[j].view(rows1, pitch1)[:, 0]),
+        "tp_pack": lambda j: tp.pack_async(typed1[j], 1, t1, packed1, rows1, 0, stream),
+        "torch_scatter": lambda j: typed1[j].view(rows1, pitch1)[:, 0].copy_(packed1),
+        "tp_unpack": lambda j: tp.unpack_async(packed1, rows1, 0, typed1[j], 1, t1, stream),
+    }
+    narrow = {"rows": rows1, "pitch": pitch1, "run_bytes": 1}
+    for name, op in ops.items():
+        def rotating(op=op):
+            op(k[0] % 2)
+            k[0] += 1
+        us = timed(rotating, n=8, warm=2)
+        narrow[name + "_us"] = round(us, 1)
+        narrow[name + "_rows_per_ns"] = round(rows1 / us / 1e3, 2)
+    res["one_byte_rows_vs_torch_strided_copy"] = narrow
+    del typed1, packed1
+
     # synchronous-call latency (launch + kernel + synchronize, the paper's timed region) on the small 2D vector
     c1 = W.configs.cfg1()
     buf = torch.zeros(c1["buffer_bytes"], dtype=torch.uint8, device=dev)
