@@ -67,7 +67,8 @@ enum {
     TP_ERR_ARG = 3,      /* null out-pointer, ndims out of [1, TP_MAX_DIMS], bad subarray box, bad order,
                             negative position or buffer size, unknown override key                    */
     TP_ERR_TRUNCATE = 4, /* *position + count*size exceeds the contiguous buffer's size               */
-    TP_ERR_BUFFER = 5,   /* null data pointer with bytes to move, or memory the GPU cannot address    */
+    TP_ERR_BUFFER = 5,   /* null data pointer with bytes to move, or memory the GPU cannot address
+                            (pageable host memory, or a request that ends outside its buffer)         */
     TP_ERR_OTHER = 6,    /* HIP runtime failure (no device, launch error); see tp_error_string        */
     TP_ERR_RANGE = 7     /* a size, extent or canonical form overflows int64 or exceeds TP_MAX_DIMS   */
 };
@@ -120,7 +121,11 @@ int tp_pack_size(int incount, tp_type t, int64_t *size);
  * Memory: the typed (non-contiguous) buffer - inbuf of pack, outbuf of unpack - must be DEVICE
  * memory.  The contiguous buffer may be device memory or pinned, GPU-mapped host memory
  * (hipHostMalloc): the latter is the zero-copy path of Sec. 4.  Pageable host memory gives
- * TP_ERR_BUFFER.  `hip_stream` is a hipStream_t (NULL = the default stream).
+ * TP_ERR_BUFFER.  So does a request that runs past its buffers: on each side the first, the
+ * lowest and the highest byte the call would touch are checked to be memory of the right kind
+ * (not every byte in between), so that a datatype too large for its buffer is an error here
+ * rather than a memory fault on the device.  `hip_stream` is a hipStream_t (NULL = the default
+ * stream).
  *
  * tp_pack / tp_unpack return after the data is complete (they synchronize the stream, as the
  * paper's timed region does, Sec. 6.3).  The *_async forms only enqueue on the stream; the
@@ -253,7 +258,8 @@ int tp_resource_stats(int kind, tp_resource_counts *out);
  *
  * tp_set_override(key, value): force planner choices.  Keys:
  *   "word"          "0" (automatic) or 1, 2, 4, 8, 16: upper limit on the access width in bytes
- *   "check_buffers" "1" (default) or "0": skip the per-call memory-residency query
+ *   "check_buffers" "1" (default) or "0": skip the per-call memory-residency queries (then the
+ *                   buffers are taken to be GPU-addressable and large enough: the caller's duty)
  *   "nt"            "-1" (automatic) or 0..3: streaming hints, bit 0 = non-temporal loads,
  *                   bit 1 = non-temporal stores
  *   "shift"         "1" (default) or "0": allow the shifted-copy kernel, which moves long runs

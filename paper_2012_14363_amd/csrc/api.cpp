@@ -133,6 +133,23 @@ int check_request(const void* typed_buf, int64_t count, tp_type t, const void* p
     return kSuccess;
 }
 
+// Displacements, from the origin, of the lowest and the highest byte that `count` objects of a
+// committed non-empty type select.
+int data_span(const TypeNode& node, int64_t count, int64_t* lo, int64_t* hi) {
+    const StridedBlock& sb = node.block;
+    *lo = *hi = sb.start;
+    auto widen = [&](int64_t steps, int64_t stride) {
+        int64_t reach;
+        if (__builtin_mul_overflow(steps, stride, &reach)) return false;
+        return !__builtin_add_overflow(reach < 0 ? *lo : *hi, reach, reach < 0 ? lo : hi);
+    };
+    for (int d = 1; d < sb.ndims; ++d)
+        if (!widen(sb.counts[d] - 1, sb.strides[d])) return kErrRange;
+    if (!widen(count - 1, node.extent())) return kErrRange;
+    if (__builtin_add_overflow(*hi, sb.counts[0] - 1, hi)) return kErrRange;
+    return kSuccess;
+}
+
 // Resolves the buffers of a checked request and appends its planned launches to `launches`.
 int plan_request(const TypeNode& node, const void* typed_buf, int64_t count, PackedSide* packed,
                  int64_t position, std::vector<Launch>* launches) {
@@ -142,8 +159,27 @@ int plan_request(const TypeNode& node, const void* typed_buf, int64_t count, Pac
     int rc = resolve_pointer(static_cast<const char*>(typed_buf) + node.block.start, false, &first_byte);
     if (rc != kSuccess) return rc;
     const char* typed_view = first_byte - node.block.start;
+    // So are the lowest and the highest byte the request touches: a datatype that runs past its
+    // buffer is reported here instead of as a GPU memory fault.  (Bytes in between are not
+    // queried; an allocation boundary crossed on the way to valid memory goes unnoticed.)
+    int64_t lo = 0, hi = 0;
+    rc = data_span(node, count, &lo, &hi);
+    if (rc != kSuccess) return rc;
+    for (const int64_t at : {lo, hi}) {
+        if (at == node.block.start) continue;
+        const char* ignored = nullptr;
+        rc = resolve_pointer(static_cast<const char*>(typed_buf) + at, false, &ignored);
+        if (rc != kSuccess) return rc;
+    }
     rc = packed->resolve();
     if (rc != kSuccess) return rc;
+    const int64_t bytes = count * node.size;
+    for (const int64_t at : {position, position + bytes - 1}) {
+        if (at == 0) continue;
+        const char* ignored = nullptr;
+        rc = resolve_pointer(static_cast<const char*>(packed->raw) + at, true, &ignored);
+        if (rc != kSuccess) return rc;
+    }
     PlanInput in;
     in.block = node.block;
     in.extent = node.extent();

@@ -659,6 +659,31 @@ def test_model_measure_and_host_delivery(dev, tmp_path):
     assert np.array_equal(host.numpy(), expect[4:])
 
 
+def test_datatype_running_past_its_buffer_is_refused(dev):
+    # the lowest and highest byte of a request must be memory the GPU can address; a type that
+    # leaves its buffer is an error on the host, not a fault on the device
+    far = 1 << 44  # 16 TiB: no allocation of this process reaches that far
+    buf = torch.zeros(4096, dtype=torch.uint8, device=dev)
+    out = torch.full((4096,), 0xEE, dtype=torch.uint8, device=dev)
+    for name, recipe in (("above", hvector(2, 1, far, BYTE)), ("below", hvector(2, 1, -far, BYTE)),
+                         ("objects", subarray([1 << 30, 1 << 14], [1, 1], [0, 0], "C", BYTE))):
+        h = tp.type_from_recipe(recipe)
+        count = 1 if name != "objects" else 2  # one byte per object, the second object 2^44 bytes on
+        say("span check:", name)
+        for fn, args in ((tp.pack, (buf, count, h, out, 1 << 62, 0)), (tp.unpack, (out, 1 << 62, 0, buf, count, h))):
+            with pytest.raises(tp.TpError) as e:
+                fn(*args)
+            assert e.value.code == tp.TP_ERR_BUFFER
+    # the contiguous side: a position far beyond the buffer
+    h = tp.type_from_recipe(contiguous(2, BYTE))
+    for fn, args in ((tp.pack, (buf, 1, h, out, far + 2, far)), (tp.unpack, (out, far + 2, far, buf, 1, h))):
+        with pytest.raises(tp.TpError) as e:
+            fn(*args)
+        assert e.value.code == tp.TP_ERR_BUFFER
+    torch.cuda.synchronize()
+    assert bool((out == 0xEE).all()) and bool((buf == 0).all())
+
+
 # ------------------------------------------------------------------ resource cache
 class _DeviceView:
     """Zero-copy torch view of `n` bytes of device memory at `address` (owned elsewhere)."""
