@@ -495,7 +495,7 @@ def resource_cache_timing(W, tp, torch, dev, stream):
             "leased_buffers": round(per_call_us(src_l, dst_l), 2),
             "calls": calls,
             "note": "512-byte object; the loop is Python + ctypes, equal on both sides; the difference is the "
-                    "two residency queries per call",
+                    "memory queries (one attribute and one bounds query per buffer)",
         }
     finally:
         tp.resource_release(tp.TP_RES_DEVICE, src_l)

@@ -11,6 +11,7 @@
 #include <string>
 #include <vector>
 
+#include "buffer_map.hpp"
 #include "canon.hpp"
 #include "kernels.hpp"
 #include "plan.hpp"
@@ -71,18 +72,21 @@ TypePtr committed_node(tp_type t) {
     return node->committed.load(std::memory_order_acquire) ? node : nullptr;
 }
 
-// Resolves a data pointer to an address the GPU can use.  `allow_host`: pinned,
-// GPU-mapped host memory is acceptable (the contiguous side only).
-int resolve_pointer(const void* ptr, bool allow_host, const char** device_view) {
-    if (!g_check_buffers.load(std::memory_order_relaxed)) {
-        *device_view = static_cast<const char*>(ptr);
-        return kSuccess;
-    }
+// BufferMap's query: the allocation that holds `ptr`, from the library's own leases or else from
+// the runtime.
+int query_memory(const void* ptr, MemRange* range) {
+    const uintptr_t a = reinterpret_cast<uintptr_t>(ptr);
     // buffers leased from the library's own cache are known without asking the runtime
     int kind = 0;
     int64_t room = 0;
-    if (library_resources().find_leased(ptr, &kind, device_view, &room))
-        return kind == kResDevice || allow_host ? kSuccess : kErrBuffer;
+    const char* view = nullptr;
+    if (library_resources().find_leased(ptr, &kind, &view, &room)) {
+        range->lo = a;
+        range->hi = a + static_cast<uintptr_t>(room);
+        range->host = kind != kResDevice;
+        range->view_delta = view - static_cast<const char*>(ptr);
+        return kSuccess;
+    }
     hipPointerAttribute_t attr;
     std::memset(&attr, 0, sizeof attr);
     const hipError_t e = hipPointerGetAttributes(&attr, ptr);
@@ -95,30 +99,32 @@ int resolve_pointer(const void* ptr, bool allow_host, const char** device_view) 
     switch (attr.type) {
     case hipMemoryTypeDevice:
     case hipMemoryTypeManaged:
-        *device_view = static_cast<const char*>(ptr);
-        return kSuccess;
+        range->host = false;
+        range->view_delta = 0;
+        break;
     case hipMemoryTypeHost:
-        if (!allow_host || !attr.devicePointer) return kErrBuffer;
-        *device_view = static_cast<const char*>(attr.devicePointer);
-        return kSuccess;
+        if (!attr.devicePointer) return kErrBuffer;
+        range->host = true;
+        range->view_delta = static_cast<const char*>(attr.devicePointer) - static_cast<const char*>(ptr);
+        break;
     default:
         return kErrBuffer;  // pageable host memory
     }
+    // the allocation's bounds; where the runtime does not tell, only `ptr` itself is known
+    void* base = nullptr;
+    size_t size = 0;
+    if (hipMemGetAddressRange(&base, &size, const_cast<void*>(ptr)) == hipSuccess && size > 0) {
+        range->lo = reinterpret_cast<uintptr_t>(base);
+        range->hi = range->lo + size;
+    } else {
+        (void)hipGetLastError();
+        range->lo = a;
+        range->hi = a + 1;
+    }
+    return kSuccess;
 }
 
-// The contiguous buffer of a call, resolved to a GPU-usable address on first need (after the
-// request has passed the checks that need no device).
-struct PackedSide {
-    const void* raw = nullptr;
-    const char* view = nullptr;
-    bool resolved = false;
-    int resolve() {
-        if (resolved) return kSuccess;
-        const int rc = resolve_pointer(raw, true, &view);
-        resolved = rc == kSuccess;
-        return rc;
-    }
-};
+BufferMap::Query buffer_query() { return g_check_buffers.load(std::memory_order_relaxed) ? query_memory : nullptr; }
 
 // Checks of one pack/unpack request that need no device: handle, count, fit, null buffers.
 // On success *bytes is what the request moves and *node its datatype.
@@ -150,42 +156,35 @@ int data_span(const TypeNode& node, int64_t count, int64_t* lo, int64_t* hi) {
     return kSuccess;
 }
 
-// Resolves the buffers of a checked request and appends its planned launches to `launches`.
-int plan_request(const TypeNode& node, const void* typed_buf, int64_t count, PackedSide* packed,
-                 int64_t position, std::vector<Launch>* launches) {
+// Checks the buffers of a request that has passed check_request and appends its planned launches
+// to `launches`.  `packed` is the contiguous buffer as the caller passed it.
+int plan_request(const TypeNode& node, const void* typed_buf, int64_t count, const void* packed, int64_t position,
+                 BufferMap* memory, std::vector<Launch>* launches) {
     // Query the first selected byte, not the origin: MPI lets the origin lie outside the
     // allocation (negative strides, lower bounds above zero); the data never does.
+    const char* typed = static_cast<const char*>(typed_buf);
     const char* first_byte = nullptr;
-    int rc = resolve_pointer(static_cast<const char*>(typed_buf) + node.block.start, false, &first_byte);
+    int rc = memory->locate(typed + node.block.start, false, &first_byte);
     if (rc != kSuccess) return rc;
     const char* typed_view = first_byte - node.block.start;
-    // So are the lowest and the highest byte the request touches: a datatype that runs past its
-    // buffer is reported here instead of as a GPU memory fault.  (Bytes in between are not
-    // queried; an allocation boundary crossed on the way to valid memory goes unnoticed.)
+    // So are the lowest and the highest byte the request touches, on both sides: a datatype that
+    // runs past its buffer is reported here instead of as a GPU memory fault.  (Bytes in between
+    // are not queried; an allocation boundary crossed on the way to valid memory goes unnoticed.)
     int64_t lo = 0, hi = 0;
     rc = data_span(node, count, &lo, &hi);
     if (rc != kSuccess) return rc;
-    for (const int64_t at : {lo, hi}) {
-        if (at == node.block.start) continue;
-        const char* ignored = nullptr;
-        rc = resolve_pointer(static_cast<const char*>(typed_buf) + at, false, &ignored);
-        if (rc != kSuccess) return rc;
-    }
-    rc = packed->resolve();
-    if (rc != kSuccess) return rc;
-    const int64_t bytes = count * node.size;
-    for (const int64_t at : {position, position + bytes - 1}) {
-        if (at == 0) continue;
-        const char* ignored = nullptr;
-        rc = resolve_pointer(static_cast<const char*>(packed->raw) + at, true, &ignored);
-        if (rc != kSuccess) return rc;
-    }
+    if ((rc = memory->check(typed + lo, false)) != kSuccess) return rc;
+    if ((rc = memory->check(typed + hi, false)) != kSuccess) return rc;
+    const char* packed_first = static_cast<const char*>(packed) + position;
+    const char* packed_view = nullptr;
+    if ((rc = memory->locate(packed_first, true, &packed_view)) != kSuccess) return rc;
+    if ((rc = memory->check(packed_first + count * node.size - 1, true)) != kSuccess) return rc;
     PlanInput in;
     in.block = node.block;
     in.extent = node.extent();
     in.count = count;
     in.typed = typed_view;
-    in.packed = const_cast<char*>(packed->view) + position;
+    in.packed = const_cast<char*>(packed_view);
     in.max_word_log2 = g_max_word_log2.load(std::memory_order_relaxed);
     in.nt = g_nt.load(std::memory_order_relaxed);
     in.allow_shift = g_allow_shift.load(std::memory_order_relaxed);
@@ -213,15 +212,14 @@ int transfer(bool unpack, const void* typed_buf, int64_t count, tp_type t, const
     if (!position) return kErrArg;
     if (*position < 0 || packed_size < 0) return kErrArg;
     t_last_plan.clear();
-    PackedSide packed;
-    packed.raw = packed_buf;
+    BufferMap memory(buffer_query());
     TypePtr node;
     int64_t bytes = 0;
     int rc = check_request(typed_buf, count, t, packed_buf, packed_size, *position, &node, &bytes);
     if (rc != kSuccess) return rc;
     std::vector<Launch> launches;
     if (bytes > 0) {
-        rc = plan_request(*node, typed_buf, count, &packed, *position, &launches);
+        rc = plan_request(*node, typed_buf, count, packed_buf, *position, &memory, &launches);
         if (rc != kSuccess) return rc;
     }
     const int64_t pos = *position + bytes;
@@ -251,8 +249,7 @@ int transfer_batch(bool unpack, int n, const void* const* typed_bufs, const int*
     if (n > 0 && (!typed_bufs || !counts || !types)) return kErrArg;
     if (*position < 0 || packed_size < 0) return kErrArg;
     t_last_plan.clear();
-    PackedSide packed;
-    packed.raw = packed_buf;
+    BufferMap memory(buffer_query());
     int64_t pos = *position;
     std::vector<TypePtr> nodes(static_cast<size_t>(n));
     std::vector<int64_t> offsets(static_cast<size_t>(n)), sizes(static_cast<size_t>(n));
@@ -266,7 +263,7 @@ int transfer_batch(bool unpack, int n, const void* const* typed_bufs, const int*
     std::vector<Launch> launches;
     for (int i = 0; i < n; ++i) {
         if (sizes[i] == 0) continue;
-        const int rc = plan_request(*nodes[i], typed_bufs[i], counts[i], &packed, offsets[i], &launches);
+        const int rc = plan_request(*nodes[i], typed_bufs[i], counts[i], packed_buf, offsets[i], &memory, &launches);
         if (rc != kSuccess) return rc;
     }
     std::vector<BatchParams> batches;

@@ -16,7 +16,7 @@ _lib = None
 
 
 def build(force=True):
-    deps = _SOURCES + [os.path.join(_CSRC, h) for h in ("plan.hpp", "tile_body.hpp", "fastdiv.hpp", "strided_block.hpp", "resource_cache.hpp")]
+    deps = _SOURCES + [os.path.join(_CSRC, h) for h in ("plan.hpp", "tile_body.hpp", "fastdiv.hpp", "strided_block.hpp", "resource_cache.hpp", "buffer_map.hpp")]
     stale = not os.path.exists(_LIB) or any(os.path.getmtime(d) > os.path.getmtime(_LIB) for d in deps)
     if force or stale:
         subprocess.check_call(["g++", "-O2", "-g", "-std=c++20", "-Wall", "-Wextra", "-Wno-unknown-pragmas", "-fPIC",
@@ -52,8 +52,26 @@ def _load():
         L.cache_emul_backend.argtypes = [ctypes.c_int, p64]
         L.cache_emul_hammer.argtypes = [vp, ctypes.c_int, ctypes.c_int]
         L.cache_emul_hammer.restype = i64
+        L.bufmap_emul_run.argtypes = [ctypes.c_int, p64, p64, pint, ctypes.c_int, ctypes.c_int, ctypes.c_int, p64, pint,
+                                      pint, p64]
+        L.bufmap_emul_run.restype = i64
         _lib = L
     return _lib
+
+
+def buffer_map_run(allocations, ops, bounds_known=True, checked=True):
+    """One BufferMap against made-up allocations [(lo, hi, is_host)], locating ops [(address,
+    allow_host)] in order.  Returns (queries made, [(status, view - address)])."""
+    na, no = len(allocations), len(ops)
+    lo = (ctypes.c_int64 * na)(*[a[0] for a in allocations])
+    hi = (ctypes.c_int64 * na)(*[a[1] for a in allocations])
+    host = (ctypes.c_int * na)(*[int(a[2]) for a in allocations])
+    addr = (ctypes.c_int64 * no)(*[o[0] for o in ops])
+    allow = (ctypes.c_int * no)(*[int(o[1]) for o in ops])
+    status = (ctypes.c_int * no)()
+    delta = (ctypes.c_int64 * no)()
+    q = _load().bufmap_emul_run(na, lo, hi, host, int(bounds_known), int(checked), no, addr, allow, status, delta)
+    return q, list(zip(status, delta))
 
 
 COUNT_FIELDS = ("hits", "misses", "idle", "leased", "idle_bytes", "leased_bytes")

@@ -116,3 +116,55 @@ int64_t cache_emul_hammer(void* c, int threads, int rounds) {
 }
 
 }  // extern "C"
+
+// ---- BufferMap (buffer_map.hpp) over a made-up set of allocations ---------------------------------
+#include "buffer_map.hpp"
+
+namespace {
+
+struct FakeMemory {
+    int n = 0;
+    const int64_t* lo = nullptr;
+    const int64_t* hi = nullptr;
+    const int* host = nullptr;
+    bool bounds_known = true;
+    int64_t queries = 0;
+};
+thread_local FakeMemory t_fake;
+
+int fake_query(const void* p, tp::MemRange* r) {
+    t_fake.queries++;
+    const int64_t a = reinterpret_cast<intptr_t>(p);
+    for (int i = 0; i < t_fake.n; ++i)
+        if (t_fake.lo[i] <= a && a < t_fake.hi[i]) {
+            r->lo = static_cast<uintptr_t>(t_fake.bounds_known ? t_fake.lo[i] : a);
+            r->hi = static_cast<uintptr_t>(t_fake.bounds_known ? t_fake.hi[i] : a + 1);
+            r->host = t_fake.host[i] != 0;
+            r->view_delta = r->host ? (ptrdiff_t{1} << 40) : 0;
+            return 0;
+        }
+    return 5;  // TP_ERR_BUFFER
+}
+
+}  // namespace
+
+extern "C" {
+
+// Runs `n_ops` locate() calls of one BufferMap against allocations [lo[i], hi[i]) (host[i]: mapped
+// host memory).  status[k] and delta[k] (view minus address) are filled per call; returns the
+// number of queries the map made.  checked == 0: a map without a query function.
+int64_t bufmap_emul_run(int n_alloc, const int64_t* lo, const int64_t* hi, const int* host, int bounds_known,
+                        int checked, int n_ops, const int64_t* addr, const int* allow_host, int* status,
+                        int64_t* delta) {
+    t_fake = FakeMemory{n_alloc, lo, hi, host, bounds_known != 0, 0};
+    tp::BufferMap map(checked ? fake_query : nullptr);
+    for (int k = 0; k < n_ops; ++k) {
+        const char* p = reinterpret_cast<const char*>(static_cast<intptr_t>(addr[k]));
+        const char* view = p;
+        status[k] = map.locate(p, allow_host[k] != 0, &view);
+        delta[k] = view - p;
+    }
+    return t_fake.queries;
+}
+
+}  // extern "C"

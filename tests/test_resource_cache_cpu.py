@@ -163,3 +163,24 @@ def test_concurrent_holders(cache):
         assert n["leased"] == 0 and n["leased_bytes"] == 0
         assert n["hits"] + n["misses"] > 0 and n["hits"] > 10 * n["misses"]
         assert n["idle"] == n["misses"]
+
+
+# ------------------------------------------------------------------ per-call buffer map
+def test_buffer_map_asks_once_per_allocation():
+    BUF = 5  # TP_ERR_BUFFER
+    allocs = [(0x1000, 0x2000, False), (0x2000, 0x2800, False), (0x9000, 0xA000, True)]
+    ops = [(0x1800, False), (0x1000, False), (0x1FFF, False),   # one allocation: one query
+           (0x2000, False),                                     # its neighbour: a second query
+           (0x0FFF, False), (0x2800, False),                    # just outside either: refused, and asked each time
+           (0x2800, False),
+           (0x9800, True), (0x9000, True), (0x9FFF, False),     # mapped host memory: only where allowed
+           (0x17FF, True)]
+    q, got = host_emul.buffer_map_run(allocs, ops)
+    assert got == [(0, 0)] * 4 + [(BUF, 0)] * 3 + [(0, 1 << 40), (0, 1 << 40), (BUF, 0), (0, 0)]
+    assert q == 2 + 3 + 1
+    # a runtime that does not tell the bounds: every new address is asked, repeated ones are not
+    q, got = host_emul.buffer_map_run(allocs, ops[:4] + [(0x1800, False)], bounds_known=False)
+    assert [g[0] for g in got] == [0] * 5 and q == 4
+    # checks switched off: nothing is asked, everything passes as device memory
+    q, got = host_emul.buffer_map_run(allocs, ops, checked=False)
+    assert q == 0 and got == [(0, 0)] * len(ops)
