@@ -36,34 +36,26 @@ def build(verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
-    build_commit_timing()
-    build_resource_timing()
+    for tool in C_TOOLS:
+        build_c_tool(tool)
     return LIB_PATH
 
 
+# plain-C programs that use the library through include/tp_pack.h alone
+C_TOOLS = ("commit_timing", "resource_timing", "pack_selftest")
 TIMING_EXE = os.path.join(PKG_DIR, "commit_timing")
-
-
-def build_commit_timing() -> str:
-    """The plain-C commit-time microbenchmark, linked against the library just built."""
-    subprocess.check_call([
-        "gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-I", INCLUDE, os.path.join(CSRC, "commit_timing.c"),
-        "-L", PKG_DIR, "-ltp_pack", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath-link," + "/opt/rocm/lib", "-o", TIMING_EXE,
-    ])
-    return TIMING_EXE
-
-
 RESOURCE_TIMING_EXE = os.path.join(PKG_DIR, "resource_timing")
+SELFTEST_EXE = os.path.join(PKG_DIR, "pack_selftest")
 
 
-def build_resource_timing() -> str:
-    """The plain-C resource-cache microbenchmark, linked against the library just built."""
+def build_c_tool(name: str) -> str:
+    """Compiles csrc/<name>.c with gcc and links it against the library just built."""
+    exe = os.path.join(PKG_DIR, name)
     subprocess.check_call([
-        "gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-I", INCLUDE, os.path.join(CSRC, "resource_timing.c"),
-        "-L", PKG_DIR, "-ltp_pack", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath-link," + "/opt/rocm/lib", "-o",
-        RESOURCE_TIMING_EXE,
+        "gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-I", INCLUDE, os.path.join(CSRC, name + ".c"),
+        "-L", PKG_DIR, "-ltp_pack", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath-link," + "/opt/rocm/lib", "-o", exe,
     ])
-    return RESOURCE_TIMING_EXE
+    return exe
 
 
 if __name__ == "__main__":

@@ -791,6 +791,19 @@ def test_staged_host_delivery_with_cached_staging(dev):
     tp.resource_trim()
 
 
+def test_plain_c_program_packs_and_unpacks(dev):
+    # the path driven from C through the header alone (its own process, the system's HIP runtime):
+    # buffers from the resource cache, data in and out through zero-copy calls, compared with
+    # nested loops in C
+    import subprocess
+    exe = os.path.join(os.path.dirname(tp.LIB_PATH), "pack_selftest")
+    assert os.path.exists(exe), "build the library first (python -m paper_2012_14363_amd.build)"
+    for shape in ((), ("64", "48", "40"), ("1", "1", "1"), ("63", "47", "39"), ("16", "48", "3"), ("3", "1", "40")):
+        say("pack_selftest", *shape)
+        r = subprocess.run([exe, *shape], capture_output=True, text=True, timeout=120)
+        assert r.returncode == 0 and r.stdout.startswith("ok"), (shape, r.stdout, r.stderr)
+
+
 # ------------------------------------------------------------------ maximum sizes
 def test_more_rows_than_one_launch_takes(dev):
     # 2^31 - 1 one-byte runs at stride 2: above the 2^30 rows a launch covers, so the planner splits
