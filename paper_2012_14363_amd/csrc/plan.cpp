@@ -180,12 +180,57 @@ bool batchable(const Launch& l) {
     return l.kind == kTile && l.p.nrd <= static_cast<uint32_t>(kBatchRowDims) && l.nblocks > 0;
 }
 
+namespace {
+
+BatchDesc make_desc(const Launch& l) {
+    BatchDesc d;
+    const KParams& p = l.p;
+    d.strided = p.strided;
+    d.packed = p.packed;
+    d.row_pitch = p.row_pitch;
+    d.n0 = p.n0;
+    d.nrows = p.nrows;
+    d.nxc = p.nxc;
+    d.xc_mul = p.xc_div.mul;
+    d.xc_shift = static_cast<uint8_t>(p.xc_div.shift);
+    d.bx_log2 = static_cast<uint8_t>(p.bx_log2);
+    d.word_log2 = static_cast<uint8_t>(l.word_log2);
+    d.tile = static_cast<uint8_t>(l.ux == 1 ? 0 : l.ux == 2 ? 1 : 2);
+    d.nrd = static_cast<uint8_t>(p.nrd == 0 ? 1 : p.nrd);
+    const FastDiv one = make_fastdiv(1);
+    for (int k = 0; k < kBatchRowDims; ++k) {
+        const bool used = static_cast<uint32_t>(k) < p.nrd;
+        d.rstride[k] = used ? p.rstride[k] : 0;
+        d.rcount[k] = used ? p.rcount[k] : 1;
+        d.rmul[k] = used ? p.rdiv[k].mul : one.mul;
+        d.rshift[k] = static_cast<uint8_t>(used ? p.rdiv[k].shift : one.shift);
+    }
+    return d;
+}
+
+}  // namespace
+
 void make_batches(const std::vector<Launch>& launches, std::vector<BatchParams>* batches,
                   std::vector<Launch>* singles) {
-    BatchParams cur;
+    std::vector<const Launch*> group;
+    uint64_t group_blocks = 0;
     auto flush = [&] {
-        if (cur.n > 0) batches->push_back(cur);
-        cur = BatchParams();
+        if (group.empty()) return;
+        // Largest first: workgroups are handed out in index order, so the big descriptors start
+        // while the whole chip is free and the small ones fill in behind them.  Each descriptor
+        // carries its own addresses, so the order inside a launch is free.
+        std::stable_sort(group.begin(), group.end(),
+                         [](const Launch* a, const Launch* b) { return a->nblocks > b->nblocks; });
+        BatchParams cur;
+        for (const Launch* l : group) {
+            cur.d[cur.n] = make_desc(*l);
+            cur.nblocks += l->nblocks;
+            cur.block_end[cur.n] = cur.nblocks;
+            ++cur.n;
+        }
+        batches->push_back(cur);
+        group.clear();
+        group_blocks = 0;
     };
     for (const Launch& l : launches) {
         if (!batchable(l)) {
@@ -193,34 +238,9 @@ void make_batches(const std::vector<Launch>& launches, std::vector<BatchParams>*
             continue;
         }
         // block ids stay below 2^31 so the in-kernel multiply-shift division holds
-        if (cur.n == static_cast<uint32_t>(kBatchMax) ||
-            static_cast<uint64_t>(cur.nblocks) + l.nblocks >= (uint64_t{1} << 31))
-            flush();
-        BatchDesc& d = cur.d[cur.n];
-        const KParams& p = l.p;
-        d.strided = p.strided;
-        d.packed = p.packed;
-        d.row_pitch = p.row_pitch;
-        d.n0 = p.n0;
-        d.nrows = p.nrows;
-        d.nxc = p.nxc;
-        d.xc_mul = p.xc_div.mul;
-        d.xc_shift = static_cast<uint8_t>(p.xc_div.shift);
-        d.bx_log2 = static_cast<uint8_t>(p.bx_log2);
-        d.word_log2 = static_cast<uint8_t>(l.word_log2);
-        d.tile = static_cast<uint8_t>(l.ux == 1 ? 0 : l.ux == 2 ? 1 : 2);
-        d.nrd = static_cast<uint8_t>(p.nrd == 0 ? 1 : p.nrd);
-        const FastDiv one = make_fastdiv(1);
-        for (int k = 0; k < kBatchRowDims; ++k) {
-            const bool used = static_cast<uint32_t>(k) < p.nrd;
-            d.rstride[k] = used ? p.rstride[k] : 0;
-            d.rcount[k] = used ? p.rcount[k] : 1;
-            d.rmul[k] = used ? p.rdiv[k].mul : one.mul;
-            d.rshift[k] = static_cast<uint8_t>(used ? p.rdiv[k].shift : one.shift);
-        }
-        cur.nblocks += l.nblocks;
-        cur.block_end[cur.n] = cur.nblocks;
-        ++cur.n;
+        if (group.size() == static_cast<size_t>(kBatchMax) || group_blocks + l.nblocks >= (uint64_t{1} << 31)) flush();
+        group.push_back(&l);
+        group_blocks += l.nblocks;
     }
     flush();
 }
