@@ -58,26 +58,26 @@ def sector_bound_fraction(run: int, granule: int = 128) -> float:
 # factor a plain 64 MiB copy calibrates (FETCH_SIZE reads half the known bytes: x2; WRITE_SIZE: x1).
 # Keyed by (op, a0): (bytes fetched, bytes written).
 MEASURED_TRAFFIC = {
-    ('pack', 1): (8587083965, 68945041),
-    ('pack', 2): (4293576915, 69172964),
-    ('pack', 4): (2146811106, 70657245),
-    ('pack', 8): (1073418349, 67076751),
-    ('pack', 16): (536718003, 67080590),
-    ('pack', 32): (268371350, 67078926),
-    ('pack', 64): (134203269, 67087754),
-    ('pack', 128): (67116286, 67125880),
-    ('pack', 256): (67116030, 67115773),
+    ('pack', 1): (8587607679, 68911800),
+    ('pack', 2): (4293839798, 68909561),
+    ('pack', 4): (2146952082, 70765973),
+    ('pack', 8): (1073488582, 67075217),
+    ('pack', 16): (536759071, 67090057),
+    ('pack', 32): (268393484, 67088138),
+    ('pack', 64): (134212609, 67088266),
+    ('pack', 128): (67121149, 67126263),
+    ('pack', 256): (67121149, 67123705),
     ('pack', 512): (67108864, 67108864),
-    ('unpack', 1): (90063590, 2146456044),
-    ('unpack', 2): (75308096, 1073228022),
-    ('unpack', 4): (67276616, 536614011),
-    ('unpack', 8): (67117181, 268307005),
-    ('unpack', 16): (67109760, 134153503),
-    ('unpack', 32): (67109504, 67076751),
-    ('unpack', 64): (67108992, 67076751),
-    ('unpack', 128): (67108992, 67132277),
-    ('unpack', 256): (67108992, 67120890),
-    ('unpack', 512): (67112959, 67115645),
+    ('unpack', 1): (90868866, 2146406940),
+    ('unpack', 2): (76903166, 1073203470),
+    ('unpack', 4): (67301195, 536601735),
+    ('unpack', 8): (67124348, 268300868),
+    ('unpack', 16): (67123324, 134150434),
+    ('unpack', 32): (67121277, 67075217),
+    ('unpack', 64): (67121149, 67075217),
+    ('unpack', 128): (67121277, 67118459),
+    ('unpack', 256): (67121149, 67109887),
+    ('unpack', 512): (67108864, 67108736),
 }
 
 
@@ -309,21 +309,40 @@ def extras(W, tp, torch, np, dev, stream):
     # the same copy without rotation: source and destination stay in the 256 MiB Infinity Cache
     us = timed(lambda: tp.pack_async(srcs[0], 1, byte_t, dsts[0], n, 0, stream), n=24)
     res["copy_64MiB_same_buffers_cache_assisted"] = {"us": round(us, 2), "gbs": round(2 * n / us / 1e3, 1)}
-    # the same 64 MiB copy between odd addresses (source + 1, destination + 3): the shifted-copy
-    # kernel against the byte-wide tile kernel it replaces
-    odd = n - 64
+    # the same 64 MiB copy between odd addresses (source + 1, destination + 3), of an odd length:
+    # unaligned 16-byte words against the byte-wide words that natural alignment would force
+    odd = n - 65
 
     def unaligned():
         tp.pack_async(srcs[k[0] % 12].data_ptr() + 1, 1, odd_t, dsts[k[0] % 12].data_ptr() + 3, odd, 0, stream)
         k[0] += 1
     odd_t = tp.type_from_recipe(W.contiguous(odd, W.BYTE))
     us = timed(unaligned, n=24)
-    res["copy_64MiB_odd_addresses_shifted_copy"] = {"us": round(us, 2), "gbs": round(2 * odd / us / 1e3, 1),
-                                                   "plan": tp.last_plan().strip()}
-    tp.set_override("shift", 0)
+    res["copy_64MiB_odd_addresses"] = {"us": round(us, 2), "gbs": round(2 * odd / us / 1e3, 1),
+                                      "plan": tp.last_plan().strip()}
+    tp.set_override("word", 1)
     us = timed(unaligned, n=12)
-    tp.set_override("shift", 1)
+    tp.set_override("word", 0)
     res["copy_64MiB_odd_addresses_bytewise"] = {"us": round(us, 2), "gbs": round(2 * odd / us / 1e3, 1)}
+    # rows at odd addresses (typed + 1, packed + 3): 200-byte and 67-byte runs at 512-byte pitch
+    for run in (200, 67):
+        rows_o = (48 << 20) // run
+        t_o = tp.type_from_recipe(W.vector(rows_o, run, 512, W.BYTE))
+        typed_o = [torch.empty(rows_o * 512 + 64, dtype=torch.uint8, device=dev).fill_(i + 1) for i in range(2)]
+        entry = {}
+        for label, toff, poff in (("aligned", 0, 0), ("typed+1_packed+3", 1, 3)):
+            def pk(toff=toff, poff=poff):
+                j = k[0] % 12
+                tp.pack_async(typed_o[j % 2].data_ptr() + toff, 1, t_o, dsts[j].data_ptr() + poff, rows_o * run, 0, stream)
+                k[0] += 1
+
+            def un(toff=toff, poff=poff):
+                j = k[0] % 12
+                tp.unpack_async(dsts[j].data_ptr() + poff, rows_o * run, 0, typed_o[j % 2].data_ptr() + toff, 1, t_o, stream)
+                k[0] += 1
+            entry[label] = {"pack_us": round(timed(pk, n=12), 1), "unpack_us": round(timed(un, n=12), 1)}
+        res[f"rows_of_{run}B_at_512B_pitch_48MiB"] = entry
+        del typed_o
     del srcs, dsts
 
     # the runtime's own 2D copy (the DMA-engine route the paper lists as future work, Sec. 8) on the

@@ -25,8 +25,8 @@ using namespace tp;
 
 std::atomic<int> g_max_word_log2{4};
 std::atomic<int> g_nt{-1};
-std::atomic<bool> g_allow_shift{true};
 std::atomic<bool> g_check_buffers{true};
+std::atomic<bool> g_narrow_partial_rows{true};
 std::atomic<int64_t> g_max_rows_per_launch{int64_t{1} << 30};
 std::atomic<int64_t> g_max_words_per_run{int64_t{1} << 30};
 
@@ -158,8 +158,8 @@ int data_span(const TypeNode& node, int64_t count, int64_t* lo, int64_t* hi) {
 
 // Checks the buffers of a request that has passed check_request and appends its planned launches
 // to `launches`.  `packed` is the contiguous buffer as the caller passed it.
-int plan_request(const TypeNode& node, const void* typed_buf, int64_t count, const void* packed, int64_t position,
-                 BufferMap* memory, std::vector<Launch>* launches) {
+int plan_request(bool unpack, const TypeNode& node, const void* typed_buf, int64_t count, const void* packed,
+                 int64_t position, BufferMap* memory, std::vector<Launch>* launches) {
     // Query the first selected byte, not the origin: MPI lets the origin lie outside the
     // allocation (negative strides, lower bounds above zero); the data never does.
     const char* typed = static_cast<const char*>(typed_buf);
@@ -185,9 +185,10 @@ int plan_request(const TypeNode& node, const void* typed_buf, int64_t count, con
     in.count = count;
     in.typed = typed_view;
     in.packed = const_cast<char*>(packed_view);
+    in.unpack = unpack;
+    in.narrow_partial_rows = g_narrow_partial_rows.load(std::memory_order_relaxed);
     in.max_word_log2 = g_max_word_log2.load(std::memory_order_relaxed);
     in.nt = g_nt.load(std::memory_order_relaxed);
-    in.allow_shift = g_allow_shift.load(std::memory_order_relaxed);
     in.max_rows_per_launch = g_max_rows_per_launch.load(std::memory_order_relaxed);
     in.max_words_per_run = g_max_words_per_run.load(std::memory_order_relaxed);
     std::vector<Launch> mine;
@@ -219,7 +220,7 @@ int transfer(bool unpack, const void* typed_buf, int64_t count, tp_type t, const
     if (rc != kSuccess) return rc;
     std::vector<Launch> launches;
     if (bytes > 0) {
-        rc = plan_request(*node, typed_buf, count, packed_buf, *position, &memory, &launches);
+        rc = plan_request(unpack, *node, typed_buf, count, packed_buf, *position, &memory, &launches);
         if (rc != kSuccess) return rc;
     }
     const int64_t pos = *position + bytes;
@@ -263,7 +264,8 @@ int transfer_batch(bool unpack, int n, const void* const* typed_bufs, const int*
     std::vector<Launch> launches;
     for (int i = 0; i < n; ++i) {
         if (sizes[i] == 0) continue;
-        const int rc = plan_request(*nodes[i], typed_bufs[i], counts[i], packed_buf, offsets[i], &memory, &launches);
+        const int rc =
+            plan_request(unpack, *nodes[i], typed_bufs[i], counts[i], packed_buf, offsets[i], &memory, &launches);
         if (rc != kSuccess) return rc;
     }
     std::vector<BatchParams> batches;
@@ -459,9 +461,9 @@ int tp_set_override(const char* key, const char* value) {
         g_nt.store(static_cast<int>(v));
         return kSuccess;
     }
-    if (!std::strcmp(key, "shift")) {
+    if (!std::strcmp(key, "narrow_partial_rows")) {
         if (v != 0 && v != 1) return kErrArg;
-        g_allow_shift.store(v == 1);
+        g_narrow_partial_rows.store(v == 1);
         return kSuccess;
     }
     if (!std::strcmp(key, "check_buffers")) {

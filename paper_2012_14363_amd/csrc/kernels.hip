@@ -1,8 +1,8 @@
 // Pack / unpack kernels for gfx950 (CDNA4, wave64).
 //
 // Pure data movement: the only arithmetic is address computation, so the design
-// goal is to keep as many naturally aligned, coalesced memory accesses in flight
-// as possible.  One kernel template covers every StridedBlock:
+// goal is to keep as many wide, coalesced memory accesses in flight as possible.
+// One kernel template covers every StridedBlock:
 //
 //   * a workgroup of 256 threads is a flat tile of bx lanes along the contiguous
 //     run times 256/bx rows (bx a power of two >= the run length in words, at most
@@ -11,6 +11,9 @@
 //     span per wavefront;
 //   * each thread moves UX words along the run and UR rows, issuing all of its
 //     loads before its first store;
+//   * words sit at any byte address (unaligned vector accesses), and the last word of
+//     a run is pulled back to end with the run, so neither addresses nor run lengths
+//     restrict the word width;
 //   * a row index is turned into its byte offset with multiply-shift division by
 //     the (run-time constant) dimension counts; in the tiles for long runs the row
 //     is uniform across the workgroup and that math runs on the scalar unit;
@@ -29,35 +32,28 @@ namespace {
 // Memory accesses with a streaming hint.  Every byte is touched once, so loads and
 // stores can carry the non-temporal bit (`nt`): the data then does not displace
 // other lines in L2 / Infinity Cache.  NT bit 0: loads, bit 1: stores.
+// The word is accessed through a type of alignment 1: the address may be any byte, and
+// the compiler, which knows that this target takes unaligned accesses, still emits one
+// global_load/store of the full width.
 template <int NT>
 struct DeviceMem {
     template <class W>
     __device__ __forceinline__ W load(const char* p) const {
-        if constexpr (NT & 1) return __builtin_nontemporal_load(reinterpret_cast<const W*>(p));
-        else return *reinterpret_cast<const W*>(p);
-    }
-    // a load that may cover bytes next to the run (inside the same aligned word)
-    template <class W>
-    __device__ __forceinline__ W load_straddling(const char* p) const {
-        return load<W>(p);
+        typedef W Unaligned __attribute__((aligned(1)));
+        if constexpr (NT & 1) return __builtin_nontemporal_load(reinterpret_cast<const Unaligned*>(p));
+        else return *reinterpret_cast<const Unaligned*>(p);
     }
     template <class W>
     __device__ __forceinline__ void store(char* p, const W& v) const {
-        if constexpr (NT & 2) __builtin_nontemporal_store(v, reinterpret_cast<W*>(p));
-        else *reinterpret_cast<W*>(p) = v;
+        typedef W Unaligned __attribute__((aligned(1)));
+        if constexpr (NT & 2) __builtin_nontemporal_store(v, reinterpret_cast<Unaligned*>(p));
+        else *reinterpret_cast<Unaligned*>(p) = v;
     }
 };
 
 template <int WLOG2, int UX, int UR, bool UNPACK, int NRD, int NT>
 __global__ void __launch_bounds__(kBlockThreads) tile_kernel(const KParams p) {
     tile_thread<WLOG2, UX, UR, UNPACK, NRD>(p, blockIdx.x, threadIdx.x, DeviceMem<NT>{});
-}
-
-// Long runs with unlike alignment on the two sides: aligned 4-byte words on both sides, the
-// source re-aligned in registers (tile_body.hpp: shift_thread).
-template <int UX, int UR, bool UNPACK, int NRD>
-__global__ void __launch_bounds__(kBlockThreads) shift_kernel(const KParams p) {
-    shift_thread<UX, UR, UNPACK, NRD>(p, blockIdx.x, threadIdx.x, DeviceMem<3>{});
 }
 
 // Many planned launches, of different datatypes, as one grid: a workgroup looks up
@@ -76,17 +72,13 @@ template <bool UNPACK>
 struct PickKernel {
     int nt = 3;
     KernelFn fn = nullptr;
-    template <int KIND, int WLOG2, int UX, int UR, int NRD>
+    template <int WLOG2, int UX, int UR, int NRD>
     void operator()() {
-        if constexpr (KIND == kShift) {
-            fn = shift_kernel<UX, UR, UNPACK, NRD>;
-        } else {
-            switch (nt) {
-            case 0: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 0>; break;
-            case 1: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 1>; break;
-            case 2: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 2>; break;
-            default: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 3>; break;
-            }
+        switch (nt) {
+        case 0: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 0>; break;
+        case 1: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 1>; break;
+        case 2: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 2>; break;
+        default: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 3>; break;
         }
     }
 };

@@ -22,40 +22,49 @@ int ceil_log2(uint64_t v) {
 
 // Thread-tile shape for runs of n0 words (Sec. 3.3 maps X to the run and fills the
 // block with further rows; here the block is flat and the split is a power of two).
+// Runs longer than the workgroup are cut into chunks of 256 * ux words; of ux = 1, 2, 4 the one
+// that pads the run least wins (1025 words: five chunks of 256 rather than two of 1024), the
+// larger on a tie since its row arithmetic is scalar.
 void choose_tile(uint32_t n0, Launch* l) {
-    if (n0 >= 4u * kBlockThreads) {
-        l->p.bx_log2 = 8;
-        l->ux = 4;
-        l->ur = 1;
-    } else if (n0 > static_cast<uint32_t>(kBlockThreads)) {
-        l->p.bx_log2 = 8;
-        l->ux = n0 <= 2u * kBlockThreads ? 2 : 4;
-        l->ur = 4 / l->ux;
-    } else {
+    if (n0 <= static_cast<uint32_t>(kBlockThreads)) {
         l->p.bx_log2 = static_cast<uint32_t>(ceil_log2(n0));
         l->ux = 1;
         l->ur = 4;
+        return;
     }
+    l->p.bx_log2 = 8;
+    uint64_t best = ~uint64_t{0};
+    for (int ux : {4, 2, 1}) {
+        const uint64_t chunk = static_cast<uint64_t>(kBlockThreads) * ux;
+        const uint64_t padded = (n0 + chunk - 1) / chunk * chunk;
+        if (padded < best) {
+            best = padded;
+            l->ux = ux;
+        }
+    }
+    l->ur = 4 / l->ux;
 }
 
 struct Splitter {
     const PlanInput& in;
-    int kind;
     int word_log2;
     int64_t row_pitch;  // bytes of a full run in the packed stream
     std::vector<Launch>* out;
 
-    // One launch over dims[0..nd): dims[0].count bytes per run (a multiple of the word).
+    int64_t word() const { return int64_t{1} << word_log2; }
+    // Words that cover a run of `bytes` (>= one word): the last one may overlap its neighbour.
+    uint32_t words(int64_t bytes) const { return static_cast<uint32_t>((bytes + word() - 1) >> word_log2); }
+
+    // One launch over dims[0..nd): dims[0].count bytes per run.
     void add(const std::vector<Dim>& dims, const char* typed, char* packed) {
         Launch l;
-        l.kind = kind;
         l.word_log2 = word_log2;
         KParams& p = l.p;
         p.strided = typed;
         p.packed = packed;
         p.row_pitch = row_pitch;
-        p.run_len = static_cast<uint32_t>(dims[0].count);
-        p.n0 = slots(dims[0].count);
+        p.n0 = words(dims[0].count);
+        p.tail_back = static_cast<uint32_t>((static_cast<int64_t>(p.n0) << word_log2) - dims[0].count);
         uint64_t rows = 1;
         p.nrd = 0;
         for (size_t d = 1; d < dims.size(); ++d) {
@@ -78,12 +87,6 @@ struct Splitter {
         out->push_back(l);
     }
 
-    // Lane slots along a run of `bytes`: words, or for a shifted copy the whole 4-byte words of
-    // the destination plus one slot for the ragged head and tail bytes.
-    uint32_t slots(int64_t bytes) const {
-        return static_cast<uint32_t>(kind == kShift ? (bytes >> word_log2) + 1 : bytes >> word_log2);
-    }
-
     // Largest row count for which block ids stay below 2^30 with runs of n0 words.
     int64_t row_limit(int64_t n0) const {
         Launch probe;
@@ -99,7 +102,7 @@ struct Splitter {
     void split_rows(std::vector<Dim> dims, const char* typed, char* packed) {
         int64_t rows = 1;
         for (size_t d = 1; d < dims.size(); ++d) rows *= dims[d].count;
-        const int64_t limit = row_limit(slots(dims[0].count));
+        const int64_t limit = row_limit(words(dims[0].count));
         if (rows <= limit) {
             add(dims, typed, packed);
             return;
@@ -115,15 +118,21 @@ struct Splitter {
         }
     }
 
-    // Runs longer than the per-launch word limit are cut into pieces along dimension 0.
+    // Runs longer than the per-launch word limit are cut into pieces along dimension 0.  A piece
+    // is a run of its own and needs at least one word, so a last piece shorter than that starts
+    // early instead and overlaps the piece before it (same bytes written twice).
     void split_runs(const std::vector<Dim>& dims, const char* typed, char* packed) {
-        // a shifted-copy piece also has to keep its byte length in 32 bits
-        const int64_t piece = kind == kShift ? std::min(in.max_words_per_run << word_log2, int64_t{1} << 30)
-                                             : in.max_words_per_run << word_log2;
-        for (int64_t off = 0; off < dims[0].count; off += piece) {
+        const int64_t piece = in.max_words_per_run << word_log2;
+        const int64_t total = dims[0].count;
+        for (int64_t off = 0; off < total; off += piece) {
+            int64_t at = off, len = std::min(piece, total - off);
+            if (len < word()) {
+                at = total - word();
+                len = word();
+            }
             std::vector<Dim> sub = dims;
-            sub[0].count = std::min(piece, dims[0].count - off);
-            split_rows(sub, typed + off, packed + off);
+            sub[0].count = len;
+            split_rows(sub, typed + at, packed + at);
         }
     }
 };
@@ -147,37 +156,42 @@ int plan_launches(const PlanInput& in, std::vector<Launch>* out) {
     }
     if (dims.size() - 1 > static_cast<size_t>(kMaxDims)) return kErrRange;
 
-    // Word width: the widest power of two (at most 16 bytes) that divides the run length,
-    // every stride and both start addresses, so that each access is naturally aligned.
+    // Word width.  Words may sit at any address and need not divide the run (KParams: ragged
+    // words, unaligned accesses), so the choice is free of both; measurements decide it.
+    // Reading the typed side (pack): 16 bytes wherever a run holds that much - equal to narrower
+    // words on runs they divide, up to 20 % faster on the others, and 2-4 times faster than the
+    // bytes that natural alignment would force at odd addresses or run lengths.
+    // Writing the typed side (unpack): a row that is not made of whole aligned 64-byte segments
+    // ends in partially written memory lines, which the memory system read-modify-writes, and how
+    // the row's stores are split over instructions then matters.  Measured on 60 MiB of rows at
+    // 128- to 8192-byte pitch (4 / 8 / 16-byte words, us): 100-byte rows 34 / 44 / 49, 200: 33 / 40 /
+    // 40, 1000: 29 / 33 / 35, but 1040: 34 / 27 / 27, 2056: 30 / 27 / 32, 4100: 27 / 26 / 25.  So such
+    // rows take 4-byte words up to 1 KiB and 8-byte words beyond; rows of whole aligned
+    // segments keep 16.
     const char* typed = in.typed + sb.start;
-    uint64_t bits = static_cast<uint64_t>(dims[0].count) | reinterpret_cast<uintptr_t>(typed) |
-                    reinterpret_cast<uintptr_t>(in.packed);
-    for (size_t d = 1; d < dims.size(); ++d)
-        bits |= static_cast<uint64_t>(dims[d].stride < 0 ? -dims[d].stride : dims[d].stride);
-    int word_log2 = std::min(4, in.max_word_log2);
-    if (bits != 0) word_log2 = std::min(word_log2, __builtin_ctzll(bits));
+    const int64_t run = dims[0].count;
+    int word_log2 = std::min({4, in.max_word_log2, 63 - __builtin_clzll(static_cast<uint64_t>(run))});
+    if (in.unpack && in.narrow_partial_rows && dims.size() > 1) {
+        uint64_t bits = static_cast<uint64_t>(run) | reinterpret_cast<uintptr_t>(typed);
+        for (size_t d = 1; d < dims.size(); ++d)
+            bits |= static_cast<uint64_t>(dims[d].stride < 0 ? -dims[d].stride : dims[d].stride);
+        if (bits & 63u) word_log2 = std::min(word_log2, run <= 1024 ? 2 : 3);
+    }
     // Runs of at most 32 bytes: every run costs a whole 128-byte line whatever the word, and a
     // wavefront whose lanes share rows touches fewer lines per instruction.  Measured: gathers run
     // 5-13 % faster with four (or more) lanes per row than with one wide word per row, so cap the
     // word at a quarter of the run, and at 4 bytes.
-    if (dims.size() > 1 && dims[0].count <= 32) {
-        const int quarter_log2 = dims[0].count >= 4 ? 63 - __builtin_clzll(static_cast<uint64_t>(dims[0].count / 4)) : 0;
+    if (dims.size() > 1 && run <= 32) {
+        const int quarter_log2 = run >= 4 ? 63 - __builtin_clzll(static_cast<uint64_t>(run / 4)) : 0;
         word_log2 = std::min(word_log2, std::min(2, quarter_log2));
     }
-
-    // Long runs that only byte- or 2-byte-wide words would fit move through the shifted copy.
-    int kind = kTile;
-    if (in.allow_shift && word_log2 < 2 && in.max_word_log2 >= 2 && dims[0].count >= 64) {
-        kind = kShift;
-        word_log2 = 2;
-    }
-    Splitter s{in, kind, word_log2, dims[0].count, out};
+    Splitter s{in, word_log2, run, out};
     s.split_runs(dims, typed, in.packed);
     return kSuccess;
 }
 
 bool batchable(const Launch& l) {
-    return l.kind == kTile && l.p.nrd <= static_cast<uint32_t>(kBatchRowDims) && l.nblocks > 0;
+    return l.p.nrd <= static_cast<uint32_t>(kBatchRowDims) && l.nblocks > 0;
 }
 
 namespace {
@@ -195,7 +209,7 @@ BatchDesc make_desc(const Launch& l) {
     d.xc_shift = static_cast<uint8_t>(p.xc_div.shift);
     d.bx_log2 = static_cast<uint8_t>(p.bx_log2);
     d.word_log2 = static_cast<uint8_t>(l.word_log2);
-    d.tile = static_cast<uint8_t>(l.ux == 1 ? 0 : l.ux == 2 ? 1 : 2);
+    d.tile = static_cast<uint8_t>((l.ux == 1 ? 0 : l.ux == 2 ? 1 : 2) | (p.tail_back << 4));
     d.nrd = static_cast<uint8_t>(p.nrd == 0 ? 1 : p.nrd);
     const FastDiv one = make_fastdiv(1);
     for (int k = 0; k < kBatchRowDims; ++k) {
@@ -259,8 +273,8 @@ std::string describe(const std::vector<Launch>& launches) {
     std::string text;
     char line[256];
     for (const Launch& l : launches) {
-        std::snprintf(line, sizeof line, "%s W=%d ux=%d ur=%d nt=%d bx=%u n0=%u rows=%u nrd=%u blocks=%u\n",
-                      l.kind == kShift ? "shift" : "tile", 1 << l.word_log2, l.ux, l.ur, l.nt, 1u << l.p.bx_log2, l.p.n0, l.p.nrows, l.p.nrd, l.nblocks);
+        std::snprintf(line, sizeof line, "tile W=%d ux=%d ur=%d nt=%d bx=%u n0=%u back=%u rows=%u nrd=%u blocks=%u\n",
+                      1 << l.word_log2, l.ux, l.ur, l.nt, 1u << l.p.bx_log2, l.p.n0, l.p.tail_back, l.p.nrows, l.p.nrd, l.nblocks);
         text += line;
     }
     return text;

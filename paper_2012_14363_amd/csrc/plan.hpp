@@ -20,30 +20,30 @@ constexpr int kBlockThreads = 256;  // four wave64 per workgroup
 // The launch covers `nrows` runs of `n0` words of W bytes.  Row r is element
 // (i_0, i_1, ...) of the row dimensions (r = i_0 + rcount[0]*(i_1 + ...)); its
 // bytes sit at strided + sum(i_d * rstride[d]) and at packed + r * row_pitch.
+//
+// Words are "ragged": a run whose length is no multiple of W still moves in whole words, the
+// last one pulled back by `tail_back` bytes so that it ends with the run and overlaps its
+// neighbour (the overlap is written twice with the same bytes).  Neither side needs any
+// alignment: the hardware takes unaligned vector accesses (the amdhsa ABI runs with
+// SH_MEM_CONFIG.alignment_mode = unaligned, and the compiler is told so by the word types).
 struct KParams {
     const char* strided = nullptr;  // typed buffer: origin + start (+ split offset)
     char* packed = nullptr;         // contiguous buffer + position (+ split offset)
     int64_t row_pitch = 0;          // bytes between consecutive rows in the packed stream
-    uint32_t n0 = 0;                // words per run
+    uint32_t n0 = 0;                // words per run = ceil(run bytes / W)
     uint32_t nrows = 0;
     uint32_t bx_log2 = 0;           // lanes along a run = 1 << bx_log2; the other lanes take further rows
     uint32_t nxc = 1;               // x-chunks per row; block id = row_chunk * nxc + x_chunk
     uint32_t nrd = 0;               // row dimensions in use
-    uint32_t run_len = 0;           // shifted-copy launches: bytes per run (n0 = run_len / 4 + 1 slots)
+    uint32_t tail_back = 0;         // n0 * W - run bytes (0 .. W-1): how far the last word is pulled back
     FastDiv xc_div;
     FastDiv rdiv[kMaxDims];
     uint32_t rcount[kMaxDims] = {};
     int64_t rstride[kMaxDims] = {};
 };
 
-// kTile: every access is naturally aligned on both sides with one word width.
-// kShift: long runs whose two sides are not aligned alike (odd addresses, odd run lengths):
-// 4-byte words on both sides, re-aligned in registers (see shift_thread).
-enum LaunchKind : int { kTile = 0, kShift = 1 };
-
 struct Launch {
     KParams p;
-    int kind = kTile;
     int word_log2 = 0;  // W = 1 << word_log2 bytes per lane access
     int ux = 1;         // words per thread along the run
     int ur = 1;         // rows per thread
@@ -57,9 +57,10 @@ struct PlanInput {
     int64_t count = 0;       // objects
     const char* typed = nullptr;   // origin of object 0 in the typed buffer
     char* packed = nullptr;        // contiguous buffer + position
+    bool unpack = false;     // direction: the typed side is written
+    bool narrow_partial_rows = true;  // override: unpack rows of partial 64-byte segments in 4-byte words
     int max_word_log2 = 4;   // override: cap on the access width
     int nt = -1;             // override: streaming hints (-1 = planner's choice)
-    bool allow_shift = true; // override: permit the shifted-copy kernel
     int64_t max_rows_per_launch = int64_t{1} << 30;   // tests lower these to force splitting
     int64_t max_words_per_run = int64_t{1} << 30;
 };
@@ -83,7 +84,7 @@ struct BatchDesc {
     uint32_t n0, nrows, nxc, xc_mul;
     uint8_t rshift[kBatchRowDims];
     uint8_t xc_shift, bx_log2, word_log2;
-    uint8_t tile;  // 0: (ux,ur) = (1,4); 1: (2,2); 2: (4,1)
+    uint8_t tile;  // bits 0-1: 0 = (ux,ur) (1,4), 1 = (2,2), 2 = (4,1); bits 4-7: tail_back
     uint8_t nrd;   // 1..kBatchRowDims
 };
 static_assert(sizeof(BatchDesc) == 96, "BatchDesc must stay 96 bytes");

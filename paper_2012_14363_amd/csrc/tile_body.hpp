@@ -50,7 +50,8 @@ TP_HD inline int64_t row_offset(uint32_t r, const P& p) {
 
 // Thread `tid` of workgroup `block`.  The workgroup is a flat tile of
 // bx = 1 << bx_log2 lanes along the run by 256/bx rows; this thread moves UX words
-// of each of UR rows.  `Mem` supplies load/store (plain accesses on the device).
+// of each of UR rows.  `Mem` supplies load/store of words at any byte address (plain,
+// possibly unaligned accesses on the device).
 // `P` is KParams, or the register-resident SmallParams a batched launch unpacks.
 template <int WLOG2, int UX, int UR, bool UNPACK, int NRD, class P, class Mem>
 TP_HD inline void tile_thread(const P& p, uint32_t block, uint32_t tid, Mem mem) {
@@ -82,7 +83,9 @@ TP_HD inline void tile_thread(const P& p, uint32_t block, uint32_t tid, Mem mem)
         for (int ux = 0; ux < UX; ++ux) {
             const uint32_t x = x0 + (static_cast<uint32_t>(ux) << bx_log2);
             ok[ur][ux] = row_ok && x < p.n0;
-            const int64_t xb = static_cast<int64_t>(x) << WLOG2;
+            // the last word of a run ends with the run (it overlaps the word before it if the
+            // run length is no multiple of the word)
+            const int64_t xb = (static_cast<int64_t>(x) << WLOG2) - (x + 1u == p.n0 ? p.tail_back : 0u);
             const char* s = p.strided + soff + xb;
             char* q = p.packed + poff + xb;
             src[ur][ux] = UNPACK ? q : s;
@@ -100,102 +103,6 @@ TP_HD inline void tile_thread(const P& p, uint32_t block, uint32_t tid, Mem mem)
 #pragma unroll
         for (int ux = 0; ux < UX; ++ux)
             if (ok[ur][ux]) mem.template store<W>(dst[ur][ux], v[ur][ux]);
-}
-
-// ------------------------------------------------------------------ shifted copy
-// Runs whose source and destination are not aligned alike (odd addresses, odd run lengths)
-// would otherwise move byte by byte.  Here the destination row is cut into a head of bytes up
-// to its first 4-byte boundary, whole aligned 4-byte words, and a tail of bytes.  Lane
-// x < nb builds destination word x from the two aligned source words that straddle it (a
-// funnel shift by the rows' relative misalignment) and stores it aligned; lane x == nb copies
-// the head and tail bytes.  Every store is exact: no byte outside the run is written.  A
-// source load may cover bytes outside the run, but always inside an aligned word that also
-// holds a byte of the run, hence inside a mapped page.
-TP_HD inline uint32_t funnel_shift_bytes(uint32_t lo, uint32_t hi, uint32_t bytes) {
-    return static_cast<uint32_t>(((static_cast<uint64_t>(hi) << 32) | lo) >> (8u * bytes));
-}
-
-template <int UX, int UR, bool UNPACK, int NRD, class P, class Mem>
-TP_HD inline void shift_thread(const P& p, uint32_t block, uint32_t tid, Mem mem) {
-    // 4-byte words: measured faster than 16-byte words here (31 vs 42 us for 64 MiB), and as fast
-    // as any width in the plain tile kernel
-    constexpr int WLOG2 = 2;
-    using W = uint32_t;
-    constexpr uint32_t kWordBytes = 1u << WLOG2;
-    constexpr bool kWholeGroupOnOneRow = UX > 1;
-    const uint32_t bx_log2 = kWholeGroupOnOneRow ? 8u : p.bx_log2;
-    const uint32_t tx = kWholeGroupOnOneRow ? tid : tid & ((1u << bx_log2) - 1u);
-    const uint32_t tr = kWholeGroupOnOneRow ? 0u : tid >> bx_log2;
-    const uint32_t br = static_cast<uint32_t>(kBlockThreads) >> bx_log2;
-    const uint32_t rc = fastdiv(block, p.xc_div);
-    const uint32_t xc = block - rc * p.nxc;
-    const uint32_t x0 = ((xc * UX) << bx_log2) + tx;
-    const uint32_t r0 = rc * (br * UR) + tr;
-    const uint32_t len = p.run_len;
-
-    const char* src_word[UR][UX];  // aligned source word holding the destination word's first byte
-    char* dst_word[UR][UX];
-    uint32_t shift[UR];
-    int role[UR][UX];  // 0: idle, 1: whole word, 2: head and tail bytes
-    const char* src_row[UR];
-    char* dst_row[UR];
-    uint32_t head[UR], body_words[UR];
-#pragma unroll
-    for (int ur = 0; ur < UR; ++ur) {
-        const uint32_t r = r0 + ur * br;
-        const bool row_ok = r < p.nrows;
-        const uint32_t rr = row_ok ? r : 0u;
-        const char* s = p.strided + row_offset<NRD>(rr, p);
-        char* q = p.packed + static_cast<int64_t>(rr) * p.row_pitch;
-        src_row[ur] = UNPACK ? q : s;
-        dst_row[ur] = UNPACK ? const_cast<char*>(s) : q;
-        const uint32_t to_boundary =
-            static_cast<uint32_t>(-reinterpret_cast<uintptr_t>(dst_row[ur])) & (kWordBytes - 1u);
-        head[ur] = to_boundary < len ? to_boundary : len;
-        body_words[ur] = (len - head[ur]) >> WLOG2;
-        const uintptr_t first = reinterpret_cast<uintptr_t>(src_row[ur]) + head[ur];
-        shift[ur] = static_cast<uint32_t>(first & (kWordBytes - 1u));
-#pragma unroll
-        for (int ux = 0; ux < UX; ++ux) {
-            const uint32_t x = x0 + (static_cast<uint32_t>(ux) << bx_log2);
-            role[ur][ux] = !row_ok ? 0 : x < body_words[ur] ? 1 : x == body_words[ur] ? 2 : 0;
-            const int64_t xb = static_cast<int64_t>(x) << WLOG2;
-            src_word[ur][ux] = src_row[ur] + head[ur] - shift[ur] + xb;
-            dst_word[ur][ux] = dst_row[ur] + head[ur] + xb;
-        }
-    }
-    // Loads are unconditional so that all of a thread's loads are in flight together: lanes
-    // with no word to move, and the second load of a row that needs no shift, re-read an address
-    // that is always valid - the aligned word holding the run's first byte.
-    W lo[UR][UX], hi[UR][UX];
-#pragma unroll
-    for (int ur = 0; ur < UR; ++ur) {
-        const char* safe = src_row[ur] - (reinterpret_cast<uintptr_t>(src_row[ur]) & (kWordBytes - 1u));
-#pragma unroll
-        for (int ux = 0; ux < UX; ++ux) {
-            const char* first = role[ur][ux] == 1 ? src_word[ur][ux] : safe;
-            const char* second = (role[ur][ux] == 1 && shift[ur] != 0u) ? src_word[ur][ux] + kWordBytes : first;
-            lo[ur][ux] = mem.template load_straddling<W>(first);
-            hi[ur][ux] = mem.template load_straddling<W>(second);
-        }
-    }
-#pragma unroll
-    for (int ur = 0; ur < UR; ++ur)
-#pragma unroll
-        for (int ux = 0; ux < UX; ++ux)
-            if (role[ur][ux] == 1)
-                mem.template store<W>(dst_word[ur][ux], funnel_shift_bytes(lo[ur][ux], hi[ur][ux], shift[ur]));
-    // ragged ends, one lane per row
-#pragma unroll
-    for (int ur = 0; ur < UR; ++ur)
-#pragma unroll
-        for (int ux = 0; ux < UX; ++ux)
-            if (role[ur][ux] == 2) {
-                for (uint32_t k = 0; k < head[ur]; ++k)
-                    mem.template store<uint8_t>(dst_row[ur] + k, mem.template load<uint8_t>(src_row[ur] + k));
-                for (uint32_t k = head[ur] + (body_words[ur] << WLOG2); k < len; ++k)
-                    mem.template store<uint8_t>(dst_row[ur] + k, mem.template load<uint8_t>(src_row[ur] + k));
-            }
 }
 
 // Calls f.template operator()<WLOG2, UX, UR, NRD>() for the variant a launch names;
@@ -237,7 +144,7 @@ struct SmallParams {
     const char* strided;
     char* packed;
     int64_t row_pitch;
-    uint32_t n0, nrows, bx_log2, nxc, nrd;
+    uint32_t n0, nrows, bx_log2, nxc, nrd, tail_back;
     FastDiv xc_div;
     FastDiv rdiv[kBatchRowDims];
     uint32_t rcount[kBatchRowDims];
@@ -254,6 +161,7 @@ TP_HD inline SmallParams unpack_desc(const BatchDesc& d) {
     p.bx_log2 = d.bx_log2;
     p.nxc = d.nxc;
     p.nrd = d.nrd;
+    p.tail_back = d.tile >> 4;
     p.xc_div.mul = d.xc_mul;
     p.xc_div.shift = d.xc_shift;
     p.xc_div.divisor = d.nxc;
@@ -285,7 +193,7 @@ TP_HD inline void batch_thread(const BatchParams& b, uint32_t block, uint32_t ti
     const uint32_t first = j == 0 ? 0u : b.block_end[j - 1];
     const SmallParams p = unpack_desc(b.d[j]);
     const uint32_t local = block - first;
-    const uint32_t wl = b.d[j].word_log2, tile = b.d[j].tile, nrd = b.d[j].nrd;
+    const uint32_t wl = b.d[j].word_log2, tile = b.d[j].tile & 3u, nrd = b.d[j].nrd;
 #define TP_BATCH_CASE(WL, X, R, N) tile_thread<WL, X, R, UNPACK, N>(p, local, tid, mem)
 #define TP_BATCH_NRD(WL, X, R)            \
     do {                                  \
@@ -312,25 +220,11 @@ TP_HD inline void batch_thread(const BatchParams& b, uint32_t block, uint32_t ti
 }
 
 // The one place that maps a planned launch to the kernel variant that runs it: calls
-// f.template operator()<KIND, WLOG2, UX, UR, NRD>().  Shared by the device launcher and by the
-// host emulation the tests run, so a wrong mapping shows up on the CPU.
-template <int KIND, class F>
-struct KindOf {
-    F& f;
-    template <int WLOG2, int UX, int UR, int NRD>
-    void operator()() {
-        f.template operator()<KIND, WLOG2, UX, UR, NRD>();
-    }
-};
-
+// f.template operator()<WLOG2, UX, UR, NRD>().  Shared by the device launcher and by the host
+// emulation the tests run, so a wrong mapping shows up on the CPU.
 template <class F>
 inline bool dispatch_launch(const Launch& l, uint32_t nrd, F&& f) {
-    if (l.kind == kShift) {
-        KindOf<kShift, std::remove_reference_t<F>> k{f};
-        return l.word_log2 == 2 && dispatch_variant(2, l.ux, l.ur, nrd, k);
-    }
-    KindOf<kTile, std::remove_reference_t<F>> k{f};
-    return dispatch_variant(l.word_log2, l.ux, l.ur, nrd, k);
+    return dispatch_variant(l.word_log2, l.ux, l.ur, nrd, f);
 }
 
 // A launch as the kernel sees it: a single row gets one dummy row dimension so the

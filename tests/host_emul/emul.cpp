@@ -3,9 +3,10 @@
 // Compiles the library's planner (plan.cpp) and the very same per-thread kernel
 // body (tile_body.hpp) with the host compiler and runs every workgroup and thread
 // of every launch sequentially, with each memory access checked: inside the
-// buffer it belongs to, naturally aligned, and (optionally) no destination byte
-// written twice.  It exists so that index and bounds mistakes show up on the CPU
-// instead of as a GPU memory fault.  Nothing in the product path uses it.
+// buffer it belongs to, and no destination byte written a second time with a
+// different value (the last word of a run may overlap its neighbour, which writes
+// the same bytes twice).  It exists so that index and bounds mistakes show up on
+// the CPU instead of as a GPU memory fault.  Nothing in the product path uses it.
 #include <cstdint>
 #include <cstdio>
 #include <cstring>
@@ -25,7 +26,10 @@ struct Checks {
     const char* packed_hi;
     uint8_t* write_count;  // one counter per destination byte, or null
     const char* dst_lo;
-    int64_t oob = 0, misaligned = 0, rewritten = 0;
+    int64_t oob = 0;        // accesses that leave their buffer
+    int64_t unaligned = 0;  // accesses at an address that is no multiple of their width (legal)
+    int64_t rewritten = 0;  // destination bytes written again with a different value
+    int64_t duplicates = 0; // destination bytes written again with the same value
 };
 
 struct HostMem {
@@ -37,31 +41,21 @@ struct HostMem {
     W load(const char* p) const {
         W v{};
         if (!inside(p, sizeof(W))) { c->oob++; return v; }
-        if (reinterpret_cast<uintptr_t>(p) % sizeof(W)) c->misaligned++;
+        if (reinterpret_cast<uintptr_t>(p) % sizeof(W)) c->unaligned++;
         std::memcpy(&v, p, sizeof(W));
-        return v;
-    }
-    // A load allowed to cover bytes next to the buffer as long as the aligned word also holds a
-    // byte inside it (on the device such a word lies in a mapped page); outside bytes read as 0.
-    template <class W>
-    W load_straddling(const char* p) const {
-        if (reinterpret_cast<uintptr_t>(p) % sizeof(W)) c->misaligned++;
-        unsigned char bytes[sizeof(W)] = {};
-        bool any = false;
-        for (size_t i = 0; i < sizeof(W); ++i)
-            if (inside(p + i, 1)) { bytes[i] = static_cast<unsigned char>(p[i]); any = true; }
-        if (!any) c->oob++;
-        W v;
-        std::memcpy(&v, bytes, sizeof(W));
         return v;
     }
     template <class W>
     void store(char* p, const W& v) const {
         if (!inside(p, sizeof(W))) { c->oob++; return; }
-        if (reinterpret_cast<uintptr_t>(p) % sizeof(W)) c->misaligned++;
-        if (c->write_count)
+        if (reinterpret_cast<uintptr_t>(p) % sizeof(W)) c->unaligned++;
+        if (c->write_count) {
+            const char* bytes = reinterpret_cast<const char*>(&v);
             for (size_t i = 0; i < sizeof(W); ++i)
-                if (c->write_count[p - c->dst_lo + static_cast<long>(i)]++) c->rewritten++;
+                if (c->write_count[p - c->dst_lo + static_cast<long>(i)]++) {
+                    if (p[i] != bytes[i]) c->rewritten++; else c->duplicates++;
+                }
+        }
         std::memcpy(p, &v, sizeof(W));
     }
 };
@@ -72,13 +66,11 @@ struct RunLaunch {
     const tp::KParams* p;
     uint32_t nblocks;
     HostMem mem;
-    template <int KIND, int WLOG2, int UX, int UR, int NRD>
+    template <int WLOG2, int UX, int UR, int NRD>
     void operator()() {
         for (uint32_t b = 0; b < nblocks; ++b)
-            for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t) {
-                if constexpr (KIND == tp::kShift) tp::shift_thread<UX, UR, UNPACK, NRD>(*p, b, t, mem);
-                else tp::tile_thread<WLOG2, UX, UR, UNPACK, NRD>(*p, b, t, mem);
-            }
+            for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t)
+                tp::tile_thread<WLOG2, UX, UR, UNPACK, NRD>(*p, b, t, mem);
     }
 };
 
@@ -91,13 +83,14 @@ extern "C" {
 //   typed  buffer [typed_buf, typed_buf + typed_len), objects' origin at typed_buf + origin
 //   packed buffer [packed_buf, packed_buf + packed_len), data at packed_buf + position
 // write_count (may be null) has one byte per byte of the destination buffer.
-// result[0..2] = accesses out of bounds, misaligned, destination bytes written twice;
-// result[3] = number of launches.  `plan_text` receives the plan description.
+// result[0..2] = accesses out of bounds, unaligned accesses, destination bytes written again
+// with a different value; result[3] = number of launches; result[4] = destination bytes written
+// again with the same value.  `plan_text` receives the plan description.
 // Returns a TP_* status from the planner, or 100 if a launch names no kernel variant.
 int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, const int64_t* strides, int64_t extent,
                   int64_t count, char* typed_buf, int64_t typed_len, int64_t origin, char* packed_buf,
                   int64_t packed_len, int64_t position, int max_word_log2, int64_t max_rows_per_launch,
-                  int64_t max_words_per_run, int allow_shift, uint8_t* write_count, int64_t* result,
+                  int64_t max_words_per_run, uint8_t* write_count, int64_t* result,
                   char* plan_text, int64_t plan_text_len) {
     tp::PlanInput in;
     in.block.ndims = ndims;
@@ -110,10 +103,10 @@ int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, c
     in.count = count;
     in.typed = typed_buf + origin;
     in.packed = packed_buf + position;
+    in.unpack = unpack != 0;
     in.max_word_log2 = max_word_log2;
     in.max_rows_per_launch = max_rows_per_launch;
     in.max_words_per_run = max_words_per_run;
-    in.allow_shift = allow_shift != 0;
     std::vector<tp::Launch> launches;
     const int rc = tp::plan_launches(in, &launches);
     if (rc != tp::kSuccess) return rc;
@@ -136,9 +129,10 @@ int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, c
         if (!found) return 100;
     }
     result[0] = c.oob;
-    result[1] = c.misaligned;
+    result[1] = c.unaligned;
     result[2] = c.rewritten;
     result[3] = static_cast<int64_t>(launches.size());
+    result[4] = c.duplicates;
     return 0;
 }
 
@@ -174,7 +168,8 @@ int64_t emul_fastdiv_mismatches(uint32_t small_limit, int64_t random_pairs, uint
 // The batched form: n requests (request i: StridedBlock i, extent, object count, origin in the one
 // typed buffer) sharing the packed buffer from `position` on.  Plans every request, groups the
 // launches into batches exactly as the library does, and runs batch_thread for every workgroup
-// and thread.  result[3] = number of batched launches, result[4] = launches left single.
+// and thread.  result[3] = number of batched launches, result[4] = launches left single,
+// result[5] = destination bytes written again with the same value.
 int emul_transfer_batch(int unpack, int n, const int* ndims, const int64_t* starts, const int64_t* counts,
                         const int64_t* strides, const int64_t* extents, const int64_t* objects,
                         const int64_t* origins, const int64_t* sizes, char* typed_buf, int64_t typed_len,
@@ -194,6 +189,7 @@ int emul_transfer_batch(int unpack, int n, const int* ndims, const int64_t* star
         in.count = objects[i];
         in.typed = typed_buf + origins[i];
         in.packed = packed_buf + pos;
+        in.unpack = unpack != 0;
         std::vector<tp::Launch> mine;
         const int rc = tp::plan_launches(in, &mine);
         if (rc != tp::kSuccess) return rc;
@@ -224,10 +220,11 @@ int emul_transfer_batch(int unpack, int n, const int* ndims, const int64_t* star
         if (!found) return 100;
     }
     result[0] = c.oob;
-    result[1] = c.misaligned;
+    result[1] = c.unaligned;
     result[2] = c.rewritten;
     result[3] = static_cast<int64_t>(batches.size());
     result[4] = static_cast<int64_t>(singles.size());
+    result[5] = c.duplicates;
     return 0;
 }
 

@@ -60,6 +60,7 @@ def roundtrip(t, incount, dev, *, typed_shift=0, packed_shift=0, position=0, see
     packed_d = store[packed_shift:packed_shift + position + size]
     new_pos = tp.pack(typed_d.data_ptr() + origin, incount, h, packed_d, position + size, position)
     assert new_pos == position + size
+    plans = {"pack": tp.last_plan(), "unpack": ""}
     expect = np.full(position + size, 0xEE, dtype=np.uint8)
     cc.pack(typed_h, origin, incount, t, expect, position)
     got = store.cpu().numpy()
@@ -72,9 +73,11 @@ def roundtrip(t, incount, dev, *, typed_shift=0, packed_shift=0, position=0, see
         assert new_pos == position + size
         want = np.full(nbytes, 0xA5, dtype=np.uint8)
         cc.unpack(expect, position, want, origin, incount, t)
+        plans["unpack"] = tp.last_plan()
         assert np.array_equal(dst_d.cpu().numpy(), want), (t, tp.last_plan())
     if h >= 12:
         tp.type_free(h)
+    return plans
 
 
 # ------------------------------------------------------------------ small and ragged
@@ -132,11 +135,11 @@ def test_random_medium_types(dev):
         if cc.size(t) * incount > (8 << 20) or cc.extent(t) * incount > (256 << 20):
             continue
         say("medium type", i, "size", cc.size(t), "extent", cc.extent(t), "incount", incount)
-        roundtrip(t, incount, dev, typed_shift=rng.choice((0, 0, 1, 2, 3, 4, 8, 16)),
-                  packed_shift=rng.choice((0, 0, 1, 2, 3, 4, 8)), position=rng.choice((0, 0, 1, 5, 16)), seed=i)
-        kinds.update(line.split(" ux=")[0] for line in tp.last_plan().splitlines())
+        plans = roundtrip(t, incount, dev, typed_shift=rng.choice((0, 0, 1, 2, 3, 4, 8, 16)),
+                          packed_shift=rng.choice((0, 0, 1, 2, 3, 4, 8)), position=rng.choice((0, 0, 1, 5, 16)), seed=i)
+        kinds.update(line.split(" ux=")[0] for line in (plans["pack"] + plans["unpack"]).splitlines())
     say("variants seen:", sorted(kinds))
-    assert {"tile W=1", "tile W=4", "tile W=16", "shift W=4"} <= kinds
+    assert {"tile W=1", "tile W=4", "tile W=16"} <= kinds
 
 
 @pytest.mark.parametrize("a0", [1, 2, 3, 4, 8, 16, 24, 48, 64, 200, 512, 1040, 4048, 4100, 4112, 20000])
@@ -147,26 +150,31 @@ def test_tile_shapes_and_ragged_tails(dev, a0):
     roundtrip(vector(1031, a0, a0 + 16, BYTE), 1, dev, seed=a0 + 1)
 
 
-@pytest.mark.parametrize("run", [64, 67, 127, 1030, 4049, 70001])
-def test_shifted_copy_for_unlike_alignment(dev, run):
-    # long runs at odd addresses / odd lengths take the shifted-copy kernel; every relative
-    # misalignment of the two sides, exact writes (poisoned gaps), 2D and 3D
-    say("shifted copy, run", run)
+@pytest.mark.parametrize("run", [17, 33, 64, 67, 127, 1030, 4049, 70001])
+def test_ragged_runs_at_any_alignment(dev, run):
+    # runs at odd addresses and of odd lengths move in 16-byte words all the same (unaligned
+    # accesses, last word pulled back); every relative misalignment of the two sides, exact
+    # writes (poisoned gaps), 2D and 3D
+    say("ragged runs, run", run)
     rng = random.Random(run)
+    want = "tile W=16 " if run > 32 else "tile W=4 "
     for ts in (0, 1, 2, 3, 7, 13):
         for ps in (0, 1, 2, 3, 6, 15):
-            roundtrip(vector(41, run, run + rng.choice((1, 3, 5, 61)), BYTE), rng.randint(1, 2), dev,
-                      typed_shift=ts, packed_shift=ps, position=rng.randint(0, 3), seed=run + ts)
-            assert tp.last_plan().startswith("shift W=4 "), tp.last_plan()
-    roundtrip(hvector(3, 1, 9 * (run + 7), hvector(9, 1, run + 7, contiguous(run, BYTE))), 2, dev,
-              typed_shift=3, packed_shift=1, seed=run)
-    assert "shift" in tp.last_plan()
-    try:   # and with the kernel switched off the byte-wide tile kernel gives the same bytes
-        tp.set_override("shift", 0)
-        roundtrip(vector(41, run, run + 3, BYTE), 1, dev, typed_shift=1, seed=run)
-        assert "tile W=1 " in tp.last_plan()
+            plans = roundtrip(vector(41, run, run + rng.choice((1, 3, 5, 61)), BYTE), rng.randint(1, 2), dev,
+                              typed_shift=ts, packed_shift=ps, position=rng.randint(0, 3), seed=run + ts)
+            # rows that are not whole aligned 64-byte segments are written in 4-byte words, or
+            # 8-byte words beyond 1 KiB
+            narrow = "tile W=4 " if run <= 1024 else "tile W=8 "
+            assert plans["pack"].startswith(want) and plans["unpack"].startswith(narrow), plans
+    plans = roundtrip(hvector(3, 1, 9 * (run + 7), hvector(9, 1, run + 7, contiguous(run, BYTE))), 2, dev,
+                      typed_shift=3, packed_shift=1, seed=run)
+    assert want in plans["pack"]
+    try:   # and byte-wide words give the same bytes
+        tp.set_override("word", 1)
+        plans = roundtrip(vector(41, run, run + 3, BYTE), 1, dev, typed_shift=1, seed=run)
+        assert "tile W=1 " in plans["pack"] and "tile W=1 " in plans["unpack"]
     finally:
-        tp.set_override("shift", 1)
+        tp.set_override("word", 0)
 
 
 def test_sixteen_dimensions(dev):
@@ -187,8 +195,11 @@ def test_word_widths_forced(dev):
         for w in (1, 2, 4, 8, 16):
             say("forced word", w)
             tp.set_override("word", w)
-            roundtrip(t, 2, dev, seed=w)
-            assert f"W={w} " in tp.last_plan()
+            plans = roundtrip(t, 2, dev, seed=w)
+            assert f"W={w} " in plans["pack"] and f"W={min(w, 4)} " in plans["unpack"]
+            # rows of whole aligned 64-byte segments: the unpack may use the wide words too
+            plans = roundtrip(vector(300, 192, 256, BYTE), 2, dev, seed=w)
+            assert f"W={w} " in plans["pack"] and f"W={w} " in plans["unpack"]
     finally:
         tp.set_override("word", 0)
 
@@ -445,6 +456,10 @@ def test_pinned_host_packed_side(dev):
     say("pinned packed side, small types")
     roundtrip(vector(1031, 24, 40, BYTE), 2, dev, pinned_packed=True, seed=3)
     roundtrip(hvector(37, 1, 20480, contiguous(4100, BYTE)), 1, dev, pinned_packed=True, packed_shift=4, seed=4)
+    # unaligned 16-byte accesses to mapped host memory: odd address, odd run length
+    roundtrip(hvector(37, 1, 20480, contiguous(4099, BYTE)), 2, dev, pinned_packed=True, packed_shift=3, typed_shift=1,
+              position=5, seed=5)
+    roundtrip(vector(1031, 21, 40, BYTE), 2, dev, pinned_packed=True, packed_shift=1, seed=6)
     # unpack from pinned host memory as well
     t = vector(513, 16, 48, BYTE)
     h = tp.type_from_recipe(t)
@@ -834,9 +849,8 @@ def test_more_rows_than_one_launch_takes(dev):
 
 
 def test_run_longer_than_one_launch_takes(dev):
-    # one contiguous run of 2^31 - 1 bytes between odd addresses.  The shifted copy cuts it into
-    # pieces of 2^30 bytes; with that kernel switched off it moves in byte-wide words, more than the
-    # 2^30 words a launch covers along a run, so the run is cut into pieces as well
+    # one contiguous run of 2^31 - 1 bytes between odd addresses: fewer than the 2^30 words a launch
+    # covers when they are 16 bytes wide; as byte-wide words the run is cut into pieces
     n = (1 << 31) - 1
     say("max run: generating")
     src = W.fills.counter_bytes_torch(92, n + 8, dev)
@@ -844,17 +858,27 @@ def test_run_longer_than_one_launch_takes(dev):
     h = tp.type_from_recipe(contiguous(n, BYTE))
     assert tp.pack(src.data_ptr() + 1, 1, h, dst.data_ptr() + 3, n, 0) == n
     plan = tp.last_plan()
-    assert plan.count("shift W=4") == 2, plan
+    assert plan.count("tile W=16") == 1 and "back=1 " in plan, plan
     assert torch.equal(dst[3:3 + n], src[1:1 + n])
     assert int(dst[:3].sum()) == 0 and int(dst[3 + n:].sum()) == 0
     dst.zero_()
     try:
-        tp.set_override("shift", 0)
+        tp.set_override("word", 1)
         assert tp.pack(src.data_ptr() + 1, 1, h, dst.data_ptr() + 3, n, 0) == n
     finally:
-        tp.set_override("shift", 1)
+        tp.set_override("word", 0)
     plan = tp.last_plan()
     assert plan.count("tile") >= 2 and "W=1 " in plan, plan
+    assert torch.equal(dst[3:3 + n], src[1:1 + n])
+    assert int(dst[:3].sum()) == 0 and int(dst[3 + n:].sum()) == 0
+    # 16-byte words are cut as well once the limit is lowered to 2^26 words: two pieces
+    dst.zero_()
+    try:
+        tp.set_override("max_words_per_run", 1 << 26)
+        assert tp.pack(src.data_ptr() + 1, 1, h, dst.data_ptr() + 3, n, 0) == n
+    finally:
+        tp.set_override("max_words_per_run", 1 << 30)
+    assert tp.last_plan().count("tile W=16") == 2, tp.last_plan()
     assert torch.equal(dst[3:3 + n], src[1:1 + n])
     assert int(dst[:3].sum()) == 0 and int(dst[3 + n:].sum()) == 0
 
