@@ -124,8 +124,9 @@ int tp_pack_size(int incount, tp_type t, int64_t *size);
  * TP_ERR_BUFFER.  So does a request that runs past its buffers: on each side the first, the
  * lowest and the highest byte the call would touch are checked to be memory of the right kind
  * (not every byte in between), so that a datatype too large for its buffer is an error here
- * rather than a memory fault on the device.  `hip_stream` is a hipStream_t (NULL = the default
- * stream).
+ * rather than a memory fault on the device.  No alignment is required of any buffer, position,
+ * stride or run length; speed does not depend on it beyond a few percent.  `hip_stream` is a
+ * hipStream_t (NULL = the default stream).
  *
  * tp_pack / tp_unpack return after the data is complete (they synchronize the stream, as the
  * paper's timed region does, Sec. 6.3).  The *_async forms only enqueue on the stream; the
