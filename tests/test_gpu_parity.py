@@ -472,6 +472,17 @@ def test_pinned_host_packed_side(dev):
     want = np.full(ex, 0xA5, np.uint8)
     cc.unpack(packed_h, 0, want, 0, 1, t)
     assert np.array_equal(dst.cpu().numpy(), want)
+    # ... from an odd address in it, rows of odd length into an odd typed address
+    t = hvector(29, 1, 9001, contiguous(4099, BYTE))
+    h = tp.type_from_recipe(t)
+    size, ex = tp.type_size(h), tp.type_get_extent(h)[1]
+    packed_h = W.random_bytes(10, size + 7)
+    pinned = torch.from_numpy(packed_h).pin_memory()
+    dst = torch.full((ex + 3,), 0xA5, dtype=torch.uint8, device=dev)
+    assert tp.unpack(pinned.data_ptr() + 3, size + 4, 4, dst.data_ptr() + 3, 1, h) == size + 4
+    want = np.full(ex + 3, 0xA5, np.uint8)
+    cc.unpack(packed_h[3:], 4, want, 3, 1, t)
+    assert np.array_equal(dst.cpu().numpy(), want)
 
 
 def test_counter_fill_matches_on_device(dev):
