@@ -672,7 +672,7 @@ def other_workloads(W, tp, torch, arena, dev, stream):
 
     # ---- tiny runs: 2^24 runs of bl bytes at 64-byte stride (1 GiB footprint)
     rows = []
-    outs = [torch.zeros(8 << 24, dtype=torch.uint8, device=dev) for _ in range(4)]
+    outs = [torch.zeros((8 << 24) + 64, dtype=torch.uint8, device=dev) for _ in range(4)]
     for bl in W.configs.CFG4_BLOCKLENGTHS:
         p = W.configs.cfg4_point(bl)
         h = tp.type_from_recipe(p["recipe"])
@@ -685,7 +685,20 @@ def other_workloads(W, tp, torch, arena, dev, stream):
             rows.append({"blocklength": bl, "offset": off, "pack_us": round(pk, 1), "unpack_us": round(up, 1),
                          "pack_gbs": round(2 * n / pk / 1e3, 1), "unpack_gbs": round(2 * n / up / 1e3, 1),
                          "pack_footprint_gbs": round((GiB + n) / pk / 1e3, 1), "plan": plan})
+    # the same runs with the offset inside the datatype (a 2D byte subarray's start) and the packed
+    # side at an odd position
+    extra = []
+    srcs = lambda k: arena.data_ptr() + (k % 8) * 2 * GiB   # noqa: E731
+    for bl, off, pos in ((3, 5, 0), (3, 0, 1), (8, 3, 1)):
+        h = tp.type_from_recipe(W.subarray([1 << 24, 64], [1 << 24, bl], [0, off], "C", W.BYTE))
+        n = (1 << 24) * bl
+        pk = median_event_us(lambda k: tp.pack_async(srcs(k), 1, h, outs[k % 4], n + pos, pos, stream), 8)
+        plan = tp.last_plan().strip()
+        up = median_event_us(lambda k: tp.unpack_async(outs[k % 4], n + pos, pos, srcs(k), 1, h, stream), 8)
+        extra.append({"blocklength": bl, "subarray_start": off, "position": pos, "pack_us": round(pk, 1),
+                      "unpack_us": round(up, 1), "plan": plan})
     res["tiny_runs_2p24_stride64"] = rows
+    res["tiny_runs_offset_in_type_and_odd_position"] = extra
     del outs
 
     # ---- nested 4-level type, 1000 objects of 2 MiB packed
