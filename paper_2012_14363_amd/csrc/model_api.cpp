@@ -145,7 +145,10 @@ int tp_model_measure(void* hip_stream) {
             int rc = tp_type_vector(static_cast<int>(rows), static_cast<int>(block), static_cast<int>(pitch), TP_BYTE, &t);
             if (rc != kSuccess) return rc;
             rc = tp_type_commit(&t);
-            if (rc != kSuccess) return rc;
+            if (rc != kSuccess) {
+                tp_type_free(&t);
+                return rc;
+            }
             const int reps = size >= (1 << 20) ? 7 : 15;
             const size_t at = static_cast<size_t>(s) * nb + b;
             auto pack_to = [&](char* out) {
