@@ -177,7 +177,8 @@ int plan_request(bool unpack, const TypeNode& node, const void* typed_buf, int64
     if ((rc = memory->check(typed + hi, false)) != kSuccess) return rc;
     const char* packed_first = static_cast<const char*>(packed) + position;
     const char* packed_view = nullptr;
-    if ((rc = memory->locate(packed_first, true, &packed_view)) != kSuccess) return rc;
+    bool packed_on_host = false;
+    if ((rc = memory->locate(packed_first, true, &packed_view, &packed_on_host)) != kSuccess) return rc;
     if ((rc = memory->check(packed_first + count * node.size - 1, true)) != kSuccess) return rc;
     PlanInput in;
     in.block = node.block;
@@ -186,6 +187,7 @@ int plan_request(bool unpack, const TypeNode& node, const void* typed_buf, int64
     in.typed = typed_view;
     in.packed = const_cast<char*>(packed_view);
     in.unpack = unpack;
+    in.packed_on_host = packed_on_host;
     in.narrow_partial_rows = g_narrow_partial_rows.load(std::memory_order_relaxed);
     in.max_word_log2 = g_max_word_log2.load(std::memory_order_relaxed);
     in.nt = g_nt.load(std::memory_order_relaxed);

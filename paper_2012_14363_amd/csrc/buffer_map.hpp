@@ -31,8 +31,9 @@ public:
     explicit BufferMap(Query query) : query_(query) {}
 
     // Resolves `p` to the address kernels use for it.  `allow_host`: mapped host memory is
-    // acceptable (the contiguous side of a call only).
-    int locate(const void* p, bool allow_host, const char** view) {
+    // acceptable (the contiguous side of a call only); *is_host (may be null) tells which it is.
+    int locate(const void* p, bool allow_host, const char** view, bool* is_host = nullptr) {
+        if (is_host) *is_host = false;
         if (!query_) {
             *view = static_cast<const char*>(p);
             return kSuccess;
@@ -51,6 +52,7 @@ public:
             r = &known_.back();
         }
         if (r->host && !allow_host) return kErrBuffer;
+        if (is_host) *is_host = r->host;
         *view = static_cast<const char*>(p) + r->view_delta;
         return kSuccess;
     }

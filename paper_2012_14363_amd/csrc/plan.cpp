@@ -177,6 +177,10 @@ int plan_launches(const PlanInput& in, std::vector<Launch>* out) {
             bits |= static_cast<uint64_t>(dims[d].stride < 0 ? -dims[d].stride : dims[d].stride);
         if (bits & 63u) word_log2 = std::min(word_log2, run <= 1024 ? 2 : 3);
     }
+    // Reading mapped host memory across PCIe (zero-copy unpack): 16-byte loads were measured
+    // slower than 8- or 4-byte ones (4 MiB: 115 us against 87; 64 MiB: 1270 against 1180), writes
+    // to it do not care.
+    if (in.unpack && in.packed_on_host) word_log2 = std::min(word_log2, 3);
     // Runs of at most 32 bytes: every run costs a whole 128-byte line whatever the word, and a
     // wavefront whose lanes share rows touches fewer lines per instruction.  Measured: gathers run
     // 5-13 % faster with four (or more) lanes per row than with one wide word per row, so cap the
