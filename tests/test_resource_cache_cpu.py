@@ -184,3 +184,24 @@ def test_buffer_map_asks_once_per_allocation():
     # checks switched off: nothing is asked, everything passes as device memory
     q, got = host_emul.buffer_map_run(allocs, ops, checked=False)
     assert q == 0 and got == [(0, 0)] * len(ops)
+
+
+# ------------------------------------------------------------------ the library's own entry points, without a GPU
+def test_library_resource_calls_reject_bad_arguments():
+    import ctypes
+
+    from paper_2012_14363_amd import binding as tp
+    L = tp.lib()
+    h = ctypes.c_void_p()
+    assert L.tp_resource_acquire(7, 100, ctypes.byref(h)) == tp.TP_ERR_ARG
+    assert L.tp_resource_acquire(tp.TP_RES_DEVICE, -1, ctypes.byref(h)) == tp.TP_ERR_ARG
+    assert L.tp_resource_acquire(tp.TP_RES_DEVICE, 100, None) == tp.TP_ERR_ARG
+    assert L.tp_resource_release(tp.TP_RES_DEVICE, None) == tp.TP_ERR_ARG
+    assert L.tp_resource_release(tp.TP_RES_PINNED, 0x1000) == tp.TP_ERR_ARG     # never leased
+    assert L.tp_resource_stats(9, ctypes.byref(tp.ResourceCounts())) == tp.TP_ERR_ARG
+    assert L.tp_resource_stats(tp.TP_RES_EVENT, None) == tp.TP_ERR_ARG
+    for kind in range(4):
+        c = tp.resource_stats(kind)
+        assert c["leased"] >= 0 and c["idle"] >= 0 and c["leased_bytes"] >= 0
+    assert tp.resource_trim() >= 0
+    assert L.tp_resource_trim(None) == tp.TP_SUCCESS
