@@ -19,9 +19,11 @@
  *   - Handles are small integers owned by the library until tp_type_free.  A
  *     derived type keeps its own reference to its oldtype, so freeing the
  *     oldtype right after construction is legal (as in MPI).
- *   - The caller owns every data buffer.  The library allocates no device
- *     memory and keeps no per-type metadata on the device: everything a kernel
- *     needs travels in its kernel arguments (Sec. 3.3, last paragraph).
+ *   - The caller owns every data buffer.  Pack and unpack allocate no device
+ *     memory and the library keeps no per-type metadata on the device:
+ *     everything a kernel needs travels in its kernel arguments (Sec. 3.3,
+ *     last paragraph).  Only the resource cache, the staged host delivery
+ *     without a caller's staging buffer and tp_model_measure allocate.
  *   - Thread safety: the handle table is guarded by a mutex; pack/unpack calls
  *     may run concurrently on distinct streams.
  *   - There is no CPU fallback: pack/unpack need a working HIP device and
