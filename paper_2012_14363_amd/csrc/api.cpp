@@ -27,6 +27,7 @@ std::atomic<int> g_max_word_log2{4};
 std::atomic<int> g_nt{-1};
 std::atomic<bool> g_check_buffers{true};
 std::atomic<bool> g_narrow_partial_rows{true};
+std::atomic<bool> g_allow_xpose{true};
 std::atomic<int64_t> g_max_rows_per_launch{int64_t{1} << 30};
 std::atomic<int64_t> g_max_words_per_run{int64_t{1} << 30};
 
@@ -189,6 +190,7 @@ int plan_request(bool unpack, const TypeNode& node, const void* typed_buf, int64
     in.unpack = unpack;
     in.packed_on_host = packed_on_host;
     in.narrow_partial_rows = g_narrow_partial_rows.load(std::memory_order_relaxed);
+    in.allow_xpose = g_allow_xpose.load(std::memory_order_relaxed);
     in.max_word_log2 = g_max_word_log2.load(std::memory_order_relaxed);
     in.nt = g_nt.load(std::memory_order_relaxed);
     in.max_rows_per_launch = g_max_rows_per_launch.load(std::memory_order_relaxed);
@@ -461,6 +463,11 @@ int tp_set_override(const char* key, const char* value) {
     if (!std::strcmp(key, "nt")) {
         if (v < -1 || v > 3) return kErrArg;
         g_nt.store(static_cast<int>(v));
+        return kSuccess;
+    }
+    if (!std::strcmp(key, "xpose")) {
+        if (v != 0 && v != 1) return kErrArg;
+        g_allow_xpose.store(v == 1);
         return kSuccess;
     }
     if (!std::strcmp(key, "narrow_partial_rows")) {

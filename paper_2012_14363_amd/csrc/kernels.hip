@@ -56,6 +56,28 @@ __global__ void __launch_bounds__(kBlockThreads) tile_kernel(const KParams p) {
     tile_thread<WLOG2, UX, UR, UNPACK, NRD>(p, blockIdx.x, threadIdx.x, DeviceMem<NT>{});
 }
 
+// Transposing tiles through LDS (tile_body.hpp: xpose_phase1 / xpose_phase2).
+template <int WLOG2, bool UNPACK>
+__global__ void __launch_bounds__(kBlockThreads) xpose_kernel(const XParams p) {
+    using W = typename WordOf<WLOG2>::type;
+    using Tile = XposeTile<WLOG2>;
+    __shared__ W lds[Tile::kEdge * Tile::kPitch];
+    xpose_phase1<WLOG2, UNPACK>(p, blockIdx.x, threadIdx.x, DeviceMem<3>{}, lds);
+    __syncthreads();
+    xpose_phase2<WLOG2, UNPACK>(p, blockIdx.x, threadIdx.x, DeviceMem<3>{}, lds);
+}
+
+template <bool UNPACK>
+hipError_t enqueue_xpose(const Launch& l, hipStream_t stream) {
+    switch (l.word_log2) {
+    case 2: hipLaunchKernelGGL((xpose_kernel<2, UNPACK>), dim3(l.nblocks), dim3(kBlockThreads), 0, stream, l.x); break;
+    case 3: hipLaunchKernelGGL((xpose_kernel<3, UNPACK>), dim3(l.nblocks), dim3(kBlockThreads), 0, stream, l.x); break;
+    case 4: hipLaunchKernelGGL((xpose_kernel<4, UNPACK>), dim3(l.nblocks), dim3(kBlockThreads), 0, stream, l.x); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
 // Many planned launches, of different datatypes, as one grid: a workgroup looks up
 // the descriptor that owns it (binary search over at most 40 block ranges, scalar)
 // and runs the same tile body.  Saves one launch per datatype where launches are
@@ -86,6 +108,10 @@ struct PickKernel {
 }  // namespace
 
 hipError_t enqueue(const Launch& l, bool unpack, hipStream_t stream) {
+    if (l.kind == kXpose) {
+        if (l.nblocks == 0) return hipErrorInvalidValue;
+        return unpack ? enqueue_xpose<true>(l, stream) : enqueue_xpose<false>(l, stream);
+    }
     const KParams p = kernel_params(l);
     KernelFn fn = nullptr;
     if (unpack) {

@@ -137,6 +137,64 @@ struct Splitter {
     }
 };
 
+// The transposing kernel (plan.hpp: XParams) applies when every element is one word of 4, 8 or 16
+// bytes, the innermost row dimension B strides over at least a memory line, and some outer row
+// dimension A steps by exactly one element, both long enough to fill tiles.  Returns false
+// (and leaves `out` alone) when it does not apply or the launch would not fit one grid.
+bool plan_xpose(const PlanInput& in, const std::vector<Dim>& dims, const char* typed, std::vector<Launch>* out) {
+    if (!in.allow_xpose || dims.size() < 3) return false;
+    const int64_t run = dims[0].count;
+    if (run != 4 && run != 8 && run != 16) return false;
+    const int word_log2 = run == 4 ? 2 : run == 8 ? 3 : 4;
+    if (word_log2 > in.max_word_log2) return false;
+    // tests that lower the split limits mean the row-by-row kernel
+    if (in.max_rows_per_launch != (int64_t{1} << 30) || in.max_words_per_run != (int64_t{1} << 30)) return false;
+    constexpr int64_t kLine = 128, kFill = 32;
+    const Dim& b = dims[1];
+    if (b.count < kFill || (b.stride < kLine && b.stride > -kLine)) return false;
+    size_t a = 0;
+    for (size_t d = 2; d < dims.size() && a == 0; ++d)
+        if (dims[d].stride == run && dims[d].count >= kFill) a = d;
+    if (a == 0) return false;
+
+    Launch l;
+    l.kind = kXpose;
+    l.word_log2 = word_log2;
+    l.nt = 3;
+    XParams& x = l.x;
+    x.strided = typed;
+    x.packed = in.packed;
+    x.ca = static_cast<uint32_t>(dims[a].count);
+    x.cb = static_cast<uint32_t>(b.count);
+    x.tb_stride = b.stride;
+    const int64_t edge = word_log2 == 4 ? 32 : 64;
+    x.tiles_a = static_cast<uint32_t>((dims[a].count + edge - 1) / edge);
+    x.tiles_b = static_cast<uint32_t>((b.count + edge - 1) / edge);
+    x.tiles_a_div = make_fastdiv(x.tiles_a);
+    x.tiles_b_div = make_fastdiv(x.tiles_b);
+    // packed bytes per step of row dimension d: one element times the counts nested inside it
+    int64_t pstride = run;
+    uint64_t blocks = static_cast<uint64_t>(x.tiles_a) * x.tiles_b;
+    for (size_t d = 1; d < dims.size(); ++d) {
+        if (d == a) {
+            x.pa_stride = pstride;
+        } else if (d != 1 && dims[d].count != 1) {
+            x.ocount[x.nod] = static_cast<uint32_t>(dims[d].count);
+            x.odiv[x.nod] = make_fastdiv(x.ocount[x.nod]);
+            x.otstride[x.nod] = dims[d].stride;
+            x.opstride[x.nod] = pstride;
+            ++x.nod;
+            blocks *= static_cast<uint64_t>(dims[d].count);
+            if (blocks >= (uint64_t{1} << 30)) return false;
+        }
+        pstride *= dims[d].count;
+    }
+    if (blocks >= (uint64_t{1} << 30)) return false;
+    l.nblocks = static_cast<uint32_t>(blocks);
+    out->push_back(l);
+    return true;
+}
+
 }  // namespace
 
 int plan_launches(const PlanInput& in, std::vector<Launch>* out) {
@@ -169,6 +227,7 @@ int plan_launches(const PlanInput& in, std::vector<Launch>* out) {
     // rows take 4-byte words up to 1 KiB and 8-byte words beyond; rows of whole aligned
     // segments keep 16.
     const char* typed = in.typed + sb.start;
+    if (plan_xpose(in, dims, typed, out)) return kSuccess;
     const int64_t run = dims[0].count;
     int word_log2 = std::min({4, in.max_word_log2, 63 - __builtin_clzll(static_cast<uint64_t>(run))});
     if (in.unpack && in.narrow_partial_rows && dims.size() > 1) {
@@ -195,7 +254,7 @@ int plan_launches(const PlanInput& in, std::vector<Launch>* out) {
 }
 
 bool batchable(const Launch& l) {
-    return l.p.nrd <= static_cast<uint32_t>(kBatchRowDims) && l.nblocks > 0;
+    return l.kind == kTile && l.p.nrd <= static_cast<uint32_t>(kBatchRowDims) && l.nblocks > 0;
 }
 
 namespace {
@@ -277,6 +336,12 @@ std::string describe(const std::vector<Launch>& launches) {
     std::string text;
     char line[256];
     for (const Launch& l : launches) {
+        if (l.kind == kXpose) {
+            std::snprintf(line, sizeof line, "xpose W=%d a=%u b=%u outer=%u blocks=%u\n", 1 << l.word_log2, l.x.ca, l.x.cb,
+                          l.x.nod, l.nblocks);
+            text += line;
+            continue;
+        }
         std::snprintf(line, sizeof line, "tile W=%d ux=%d ur=%d nt=%d bx=%u n0=%u back=%u rows=%u nrd=%u blocks=%u\n",
                       1 << l.word_log2, l.ux, l.ur, l.nt, 1u << l.p.bx_log2, l.p.n0, l.p.tail_back, l.p.nrows, l.p.nrd, l.nblocks);
         text += line;

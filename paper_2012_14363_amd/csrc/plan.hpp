@@ -42,8 +42,35 @@ struct KParams {
     int64_t rstride[kMaxDims] = {};
 };
 
+// Parameters of the transposing kernel, for blocks whose elements (runs of exactly one word) are
+// adjacent in the typed buffer along one row dimension ("A") while the packed stream runs along
+// another ("B", the innermost row dimension): a plain row-by-row copy would touch one memory line
+// per element on one side or the other.  Workgroups move T x T element tiles through LDS instead,
+// reading along the dimension that is contiguous on the source side and writing along the one
+// that is contiguous on the destination side.  This is where the stride order the paper's
+// canonicalizer sorts by (Sec. 3.2, last pass) matters; the packed order itself stays the
+// type-map order.
+struct XParams {
+    const char* strided = nullptr;  // typed buffer: origin + start
+    char* packed = nullptr;         // contiguous buffer + position
+    uint32_t ca = 0, cb = 0;        // element counts of the two tiled dimensions
+    int64_t tb_stride = 0;          // typed bytes between B-neighbours (A-neighbours are one word apart)
+    int64_t pa_stride = 0;          // packed bytes between A-neighbours (B-neighbours are one word apart)
+    uint32_t tiles_a = 0, tiles_b = 0;
+    FastDiv tiles_a_div, tiles_b_div;
+    uint32_t nod = 0;               // remaining ("outer") row dimensions, nesting order
+    FastDiv odiv[kMaxDims];
+    uint32_t ocount[kMaxDims] = {};
+    int64_t otstride[kMaxDims] = {};  // typed bytes per step
+    int64_t opstride[kMaxDims] = {};  // packed bytes per step
+};
+
+enum LaunchKind : int { kTile = 0, kXpose = 1 };
+
 struct Launch {
     KParams p;
+    XParams x;          // kind == kXpose only
+    int kind = kTile;
     int word_log2 = 0;  // W = 1 << word_log2 bytes per lane access
     int ux = 1;         // words per thread along the run
     int ur = 1;         // rows per thread
@@ -60,6 +87,7 @@ struct PlanInput {
     bool unpack = false;     // direction: the typed side is written
     bool packed_on_host = false;   // the contiguous buffer is mapped host memory (zero-copy)
     bool narrow_partial_rows = true;  // override: unpack rows of partial 64-byte segments in 4-byte words
+    bool allow_xpose = true;          // override: permit the transposing kernel
     int max_word_log2 = 4;   // override: cap on the access width
     int nt = -1;             // override: streaming hints (-1 = planner's choice)
     int64_t max_rows_per_launch = int64_t{1} << 30;   // tests lower these to force splitting

@@ -105,6 +105,107 @@ TP_HD inline void tile_thread(const P& p, uint32_t block, uint32_t tid, Mem mem)
             if (ok[ur][ux]) mem.template store<W>(dst[ur][ux], v[ur][ux]);
 }
 
+// ------------------------------------------------------------------ transposing tiles
+// Tile edge in elements: 64 for words of up to 8 bytes, 32 for 16-byte words (the LDS tile then
+// stays below 34 KiB; a tile row is 256 to 512 contiguous bytes on either side).
+template <int WLOG2>
+struct XposeTile {
+    static constexpr int kEdge = WLOG2 == 4 ? 32 : 64;
+    static constexpr int kPitch = kEdge + 1;  // LDS row pitch in words: the column reads of the second phase spread over banks
+    static constexpr int kRowsPerPass = kBlockThreads / kEdge;
+    static constexpr int kPasses = kEdge / kRowsPerPass;
+};
+
+// Where workgroup `block` works: its tile's first element along A and B and the byte offsets of
+// the tile's outer position on both sides.
+struct XposeOrigin {
+    uint32_t a0, b0;
+    int64_t typed_off, packed_off;
+};
+
+template <int WLOG2>
+TP_HD inline XposeOrigin xpose_origin(const XParams& p, uint32_t block) {
+    constexpr uint32_t T = XposeTile<WLOG2>::kEdge;
+    uint32_t q = fastdiv(block, p.tiles_a_div);
+    const uint32_t ta = block - q * p.tiles_a;
+    uint32_t o = fastdiv(q, p.tiles_b_div);
+    const uint32_t tb = q - o * p.tiles_b;
+    XposeOrigin g;
+    g.a0 = ta * T;
+    g.b0 = tb * T;
+    g.typed_off = 0;
+    g.packed_off = 0;
+    for (uint32_t d = 0; d < p.nod; ++d) {
+        const uint32_t nq = d + 1 < p.nod ? fastdiv(o, p.odiv[d]) : 0u;
+        const uint32_t i = d + 1 < p.nod ? o - nq * p.ocount[d] : o;
+        g.typed_off += static_cast<int64_t>(i) * p.otstride[d];
+        g.packed_off += static_cast<int64_t>(i) * p.opstride[d];
+        o = nq;
+    }
+    return g;
+}
+
+// Element (a, b) of the tile's outer position, on the typed and on the packed side.
+template <int WLOG2>
+TP_HD inline const char* xpose_typed(const XParams& p, const XposeOrigin& g, uint32_t a, uint32_t b) {
+    return p.strided + g.typed_off + static_cast<int64_t>(b) * p.tb_stride + (static_cast<int64_t>(a) << WLOG2);
+}
+template <int WLOG2>
+TP_HD inline char* xpose_packed(const XParams& p, const XposeOrigin& g, uint32_t a, uint32_t b) {
+    return p.packed + g.packed_off + static_cast<int64_t>(a) * p.pa_stride + (static_cast<int64_t>(b) << WLOG2);
+}
+
+// Phase 1, thread `tid`: read the tile from the source side, lanes running along the dimension
+// that is contiguous there (A for pack, B for unpack), into lds[b][a] (row pitch kPitch words).
+// All loads are issued before the first LDS write; lanes outside the block re-read the tile's
+// first element, which always exists.
+template <int WLOG2, bool UNPACK, class Mem>
+TP_HD inline void xpose_phase1(const XParams& p, uint32_t block, uint32_t tid, Mem mem,
+                               typename WordOf<WLOG2>::type* lds) {
+    using W = typename WordOf<WLOG2>::type;
+    using Tile = XposeTile<WLOG2>;
+    const XposeOrigin g = xpose_origin<WLOG2>(p, block);
+    const uint32_t fast = tid % Tile::kEdge, slow0 = tid / Tile::kEdge;
+    W v[Tile::kPasses];
+    bool ok[Tile::kPasses];
+#pragma unroll
+    for (int k = 0; k < Tile::kPasses; ++k) {
+        const uint32_t slow = slow0 + static_cast<uint32_t>(k) * Tile::kRowsPerPass;
+        const uint32_t a = g.a0 + (UNPACK ? slow : fast), b = g.b0 + (UNPACK ? fast : slow);
+        ok[k] = a < p.ca && b < p.cb;
+        const uint32_t aa = ok[k] ? a : g.a0, bb = ok[k] ? b : g.b0;
+        v[k] = mem.template load<W>(UNPACK ? xpose_packed<WLOG2>(p, g, aa, bb) : xpose_typed<WLOG2>(p, g, aa, bb));
+    }
+#pragma unroll
+    for (int k = 0; k < Tile::kPasses; ++k) {
+        const uint32_t slow = slow0 + static_cast<uint32_t>(k) * Tile::kRowsPerPass;
+        const uint32_t la = UNPACK ? slow : fast, lb = UNPACK ? fast : slow;
+        if (ok[k]) lds[lb * Tile::kPitch + la] = v[k];
+    }
+}
+
+// Phase 2, after every thread of the workgroup has finished phase 1: write the tile to the
+// destination side, lanes running along the dimension that is contiguous there.
+template <int WLOG2, bool UNPACK, class Mem>
+TP_HD inline void xpose_phase2(const XParams& p, uint32_t block, uint32_t tid, Mem mem,
+                               const typename WordOf<WLOG2>::type* lds) {
+    using W = typename WordOf<WLOG2>::type;
+    using Tile = XposeTile<WLOG2>;
+    const XposeOrigin g = xpose_origin<WLOG2>(p, block);
+    const uint32_t fast = tid % Tile::kEdge, slow0 = tid / Tile::kEdge;
+#pragma unroll
+    for (int k = 0; k < Tile::kPasses; ++k) {
+        const uint32_t slow = slow0 + static_cast<uint32_t>(k) * Tile::kRowsPerPass;
+        const uint32_t la = UNPACK ? fast : slow, lb = UNPACK ? slow : fast;
+        const uint32_t a = g.a0 + la, b = g.b0 + lb;
+        if (a < p.ca && b < p.cb) {
+            const W v = lds[lb * Tile::kPitch + la];
+            if (UNPACK) mem.template store<W>(const_cast<char*>(xpose_typed<WLOG2>(p, g, a, b)), v);
+            else mem.template store<W>(xpose_packed<WLOG2>(p, g, a, b), v);
+        }
+    }
+}
+
 // Calls f.template operator()<WLOG2, UX, UR, NRD>() for the variant a launch names;
 // returns false if there is none.  nrd 0 and 1 share the division-free variant
 // (the caller gives a single row one dummy dimension).

@@ -74,6 +74,43 @@ struct RunLaunch {
     }
 };
 
+// A transposing launch: per workgroup, every thread's first phase, then every thread's second
+// phase (the barrier), with the workgroup's LDS tile as a host array.
+template <int WLOG2, bool UNPACK>
+void run_xpose_words(const tp::Launch& l, HostMem mem) {
+    using W = typename tp::WordOf<WLOG2>::type;
+    using Tile = tp::XposeTile<WLOG2>;
+    std::vector<W> lds(static_cast<size_t>(Tile::kEdge) * Tile::kPitch);
+    for (uint32_t b = 0; b < l.nblocks; ++b) {
+        std::memset(lds.data(), 0x5C, lds.size() * sizeof(W));
+        for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t)
+            tp::xpose_phase1<WLOG2, UNPACK>(l.x, b, t, mem, lds.data());
+        for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t)
+            tp::xpose_phase2<WLOG2, UNPACK>(l.x, b, t, mem, lds.data());
+    }
+}
+
+bool run_xpose(const tp::Launch& l, bool unpack, HostMem mem) {
+    switch (l.word_log2) {
+    case 2: unpack ? run_xpose_words<2, true>(l, mem) : run_xpose_words<2, false>(l, mem); return true;
+    case 3: unpack ? run_xpose_words<3, true>(l, mem) : run_xpose_words<3, false>(l, mem); return true;
+    case 4: unpack ? run_xpose_words<4, true>(l, mem) : run_xpose_words<4, false>(l, mem); return true;
+    default: return false;
+    }
+}
+
+// Runs one planned launch of either kind; false if it names no kernel variant.
+bool run_launch(const tp::Launch& l, bool unpack, Checks* c) {
+    if (l.kind == tp::kXpose) return run_xpose(l, unpack, HostMem{c});
+    const tp::KParams p = tp::kernel_params(l);
+    if (unpack) {
+        RunLaunch<true> run{&p, l.nblocks, HostMem{c}};
+        return tp::dispatch_launch(l, p.nrd, run);
+    }
+    RunLaunch<false> run{&p, l.nblocks, HostMem{c}};
+    return tp::dispatch_launch(l, p.nrd, run);
+}
+
 }  // namespace
 
 extern "C" {
@@ -90,7 +127,7 @@ extern "C" {
 int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, const int64_t* strides, int64_t extent,
                   int64_t count, char* typed_buf, int64_t typed_len, int64_t origin, char* packed_buf,
                   int64_t packed_len, int64_t position, int max_word_log2, int64_t max_rows_per_launch,
-                  int64_t max_words_per_run, uint8_t* write_count, int64_t* result,
+                  int64_t max_words_per_run, int allow_xpose, uint8_t* write_count, int64_t* result,
                   char* plan_text, int64_t plan_text_len) {
     tp::PlanInput in;
     in.block.ndims = ndims;
@@ -107,6 +144,7 @@ int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, c
     in.max_word_log2 = max_word_log2;
     in.max_rows_per_launch = max_rows_per_launch;
     in.max_words_per_run = max_words_per_run;
+    in.allow_xpose = allow_xpose != 0;
     std::vector<tp::Launch> launches;
     const int rc = tp::plan_launches(in, &launches);
     if (rc != tp::kSuccess) return rc;
@@ -116,18 +154,8 @@ int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, c
     }
     Checks c{typed_buf, typed_buf + typed_len, packed_buf, packed_buf + packed_len, write_count,
              unpack ? typed_buf : packed_buf};
-    for (const tp::Launch& l : launches) {
-        const tp::KParams p = tp::kernel_params(l);
-        bool found;
-        if (unpack) {
-            RunLaunch<true> run{&p, l.nblocks, HostMem{&c}};
-            found = tp::dispatch_launch(l, p.nrd, run);
-        } else {
-            RunLaunch<false> run{&p, l.nblocks, HostMem{&c}};
-            found = tp::dispatch_launch(l, p.nrd, run);
-        }
-        if (!found) return 100;
-    }
+    for (const tp::Launch& l : launches)
+        if (!run_launch(l, unpack != 0, &c)) return 100;
     result[0] = c.oob;
     result[1] = c.unaligned;
     result[2] = c.rewritten;
@@ -207,18 +235,8 @@ int emul_transfer_batch(int unpack, int n, const int* ndims, const int64_t* star
                 if (unpack) tp::batch_thread<true>(b, blk, t, HostMem{&c});
                 else tp::batch_thread<false>(b, blk, t, HostMem{&c});
             }
-    for (const tp::Launch& l : singles) {
-        const tp::KParams p = tp::kernel_params(l);
-        bool found;
-        if (unpack) {
-            RunLaunch<true> run{&p, l.nblocks, HostMem{&c}};
-            found = tp::dispatch_launch(l, p.nrd, run);
-        } else {
-            RunLaunch<false> run{&p, l.nblocks, HostMem{&c}};
-            found = tp::dispatch_launch(l, p.nrd, run);
-        }
-        if (!found) return 100;
-    }
+    for (const tp::Launch& l : singles)
+        if (!run_launch(l, unpack != 0, &c)) return 100;
     result[0] = c.oob;
     result[1] = c.unaligned;
     result[2] = c.rewritten;
