@@ -701,6 +701,32 @@ def other_workloads(W, tp, torch, arena, dev, stream):
     res["tiny_runs_offset_in_type_and_odd_position"] = extra
     del outs
 
+    # ---- a matrix walked column by column (a transpose as a datatype): one-word elements adjacent in
+    # the typed buffer along the outer dimension.  The transposing kernel (tiles through LDS) against
+    # the row-by-row kernel and against PyTorch's transposing copy of the same matrix.
+    xp = []
+    for label, elem, esz in (("float32", W.FLOAT, 4), ("float64", W.DOUBLE, 8)):
+        n = 4096
+        h = tp.type_from_recipe(W.hvector(n, 1, esz, W.vector(n, 1, n, elem)))
+        size = n * n * esz
+        outs = [torch.empty(size, dtype=torch.uint8, device=dev) for _ in range(3)]
+        mats = lambda k: arena.data_ptr() + (k % 8) * 2 * GiB   # noqa: E731
+        row = {"matrix": f"{n} x {n} {label}", "bytes": size}
+        for mode in ("tiles_through_lds", "row_by_row"):
+            tp.set_override("xpose", 1 if mode == "tiles_through_lds" else 0)
+            pk = median_event_us(lambda k: tp.pack_async(mats(k), 1, h, outs[k % 3], size, 0, stream), 9)
+            plan = tp.last_plan().strip()
+            up = median_event_us(lambda k: tp.unpack_async(outs[k % 3], size, 0, mats(k), 1, h, stream), 9)
+            row[mode] = {"pack_us": round(pk, 1), "unpack_us": round(up, 1), "pack_gbs": round(2 * size / pk / 1e3, 1),
+                         "unpack_gbs": round(2 * size / up / 1e3, 1), "plan": plan}
+        tp.set_override("xpose", 1)
+        a = torch.empty(n * n * esz, dtype=torch.uint8, device=dev).view(n, n, esz)
+        b = torch.empty(n, n, esz, dtype=torch.uint8, device=dev)
+        row["torch_transposing_copy_us"] = round(median_event_us(lambda k: b.copy_(a.transpose(0, 1)), 9), 1)
+        xp.append(row)
+        del outs, a, b
+    res["matrix_walked_by_columns"] = xp
+
     # ---- nested 4-level type, 1000 objects of 2 MiB packed
     c5 = W.configs.cfg5()
     h = tp.type_from_recipe(c5["recipe"])
