@@ -565,6 +565,10 @@ def test_batch_mixed_types_and_fallback(dev):
     assert not py.has_overlap(deep, 2)
     reqs.insert(30, (deep, 2, typed_len))
     typed_len += 2 * cc.extent(deep) + 16
+    # and a matrix walked by columns, which the transposing kernel takes (never part of a batch)
+    walked = hvector(70, 1, 8, vector(45, 1, 70, DOUBLE))
+    reqs.insert(50, (walked, 2, typed_len + 3))
+    typed_len += 3 + 2 * cc.extent(walked) + 16
     typed_h = W.random_bytes(6, typed_len)
     typed = to_dev(typed_h, dev)
     handles = [tp.type_from_recipe(t) for t, _, _ in reqs]
@@ -574,7 +578,7 @@ def test_batch_mixed_types_and_fallback(dev):
     b = tp.Batch([typed.data_ptr() + o for _, _, o in reqs], [c for _, c, _ in reqs], handles)
     assert tp.pack_batch(b, packed, total + 5, 5) == total + 5
     plan = tp.last_plan()
-    assert plan.count("batch") == 2 and plan.count("tile") >= 1, plan
+    assert plan.count("batch") == 2 and plan.count("tile") >= 1 and plan.count("xpose") == 1, plan
     expect = np.full(total + 5, 0xEE, np.uint8)
     pos = 5
     for t, c, o in reqs:

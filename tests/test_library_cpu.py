@@ -434,8 +434,9 @@ def test_emulated_batch_of_different_types():
     # 71 requests of assorted types into one packed stream: batched launches of up to 40 requests,
     # plus the requests with too many row dimensions for a batch descriptor, which stay single launches
     rng = random.Random(77)
-    types = _random_types(305, 70, allow_negative=False)
+    types = _random_types(305, 69, allow_negative=False)
     types.insert(20, hvector(2, 1, 9000, hvector(3, 1, 1500, hvector(2, 1, 700, vector(3, 2, 100, hvector(2, 1, 40, INT16))))))
+    types.insert(40, hvector(40, 1, 4, vector(33, 1, 40, FLOAT)))    # a transposing launch: stays single
     reqs, recipes = [], []
     typed_len = 0
     for t in types:
