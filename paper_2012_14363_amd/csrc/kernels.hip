@@ -56,23 +56,31 @@ __global__ void __launch_bounds__(kBlockThreads) tile_kernel(const KParams p) {
     tile_thread<WLOG2, UX, UR, UNPACK, NRD>(p, blockIdx.x, threadIdx.x, DeviceMem<NT>{});
 }
 
-// Transposing tiles through LDS (tile_body.hpp: xpose_phase1 / xpose_phase2).
+// Transposing tiles through LDS (tile_body.hpp: xpose_phase).
 template <int WLOG2, bool UNPACK>
 __global__ void __launch_bounds__(kBlockThreads) xpose_kernel(const XParams p) {
     using W = typename WordOf<WLOG2>::type;
-    using Tile = XposeTile<WLOG2>;
-    __shared__ W lds[Tile::kEdge * Tile::kPitch];
-    xpose_phase1<WLOG2, UNPACK>(p, blockIdx.x, threadIdx.x, DeviceMem<3>{}, lds);
+    __shared__ W lds[XposeTile<WLOG2>::kLdsWords];
+    xpose_phase<WLOG2, UNPACK, true>(p, blockIdx.x, threadIdx.x, DeviceMem<3>{}, lds);
     __syncthreads();
-    xpose_phase2<WLOG2, UNPACK>(p, blockIdx.x, threadIdx.x, DeviceMem<3>{}, lds);
+    xpose_phase<WLOG2, UNPACK, false>(p, blockIdx.x, threadIdx.x, DeviceMem<3>{}, lds);
 }
 
 template <bool UNPACK>
 hipError_t enqueue_xpose(const Launch& l, hipStream_t stream) {
+    // what the kernel's LDS tile assumes of its parameters
+    const uint64_t fast = static_cast<uint64_t>(xpose_fast_words(l.word_log2));
+    const XParams& x = l.x;
+    if (x.ew == 0 || x.te == 0 || uint64_t{x.te} * x.ew > fast || x.pitch < x.te * x.ew ||
+        uint64_t{x.te} * x.pitch > fast * (fast + 32))
+        return hipErrorInvalidValue;
+    const dim3 grid(l.nblocks), block(kBlockThreads);
     switch (l.word_log2) {
-    case 2: hipLaunchKernelGGL((xpose_kernel<2, UNPACK>), dim3(l.nblocks), dim3(kBlockThreads), 0, stream, l.x); break;
-    case 3: hipLaunchKernelGGL((xpose_kernel<3, UNPACK>), dim3(l.nblocks), dim3(kBlockThreads), 0, stream, l.x); break;
-    case 4: hipLaunchKernelGGL((xpose_kernel<4, UNPACK>), dim3(l.nblocks), dim3(kBlockThreads), 0, stream, l.x); break;
+    case 0: hipLaunchKernelGGL((xpose_kernel<0, UNPACK>), grid, block, 0, stream, l.x); break;
+    case 1: hipLaunchKernelGGL((xpose_kernel<1, UNPACK>), grid, block, 0, stream, l.x); break;
+    case 2: hipLaunchKernelGGL((xpose_kernel<2, UNPACK>), grid, block, 0, stream, l.x); break;
+    case 3: hipLaunchKernelGGL((xpose_kernel<3, UNPACK>), grid, block, 0, stream, l.x); break;
+    case 4: hipLaunchKernelGGL((xpose_kernel<4, UNPACK>), grid, block, 0, stream, l.x); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

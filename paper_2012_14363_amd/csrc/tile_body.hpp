@@ -106,14 +106,11 @@ TP_HD inline void tile_thread(const P& p, uint32_t block, uint32_t tid, Mem mem)
 }
 
 // ------------------------------------------------------------------ transposing tiles
-// Tile edge in elements: 64 for words of up to 8 bytes, 32 for 16-byte words (the LDS tile then
-// stays below 34 KiB; a tile row is 256 to 512 contiguous bytes on either side).
 template <int WLOG2>
 struct XposeTile {
-    static constexpr int kEdge = WLOG2 == 4 ? 32 : 64;
-    static constexpr int kPitch = kEdge + 1;  // LDS row pitch in words: the column reads of the second phase spread over banks
-    static constexpr int kRowsPerPass = kBlockThreads / kEdge;
-    static constexpr int kPasses = kEdge / kRowsPerPass;
+    static constexpr int kFast = xpose_fast_words(WLOG2);  // lanes (words) along a tile row
+    static constexpr int kRowsPerPass = kBlockThreads / kFast;
+    static constexpr int kLdsWords = kFast * (kFast + 32);  // te rows of `pitch` words at most
 };
 
 // Where workgroup `block` works: its tile's first element along A and B and the byte offsets of
@@ -123,16 +120,14 @@ struct XposeOrigin {
     int64_t typed_off, packed_off;
 };
 
-template <int WLOG2>
 TP_HD inline XposeOrigin xpose_origin(const XParams& p, uint32_t block) {
-    constexpr uint32_t T = XposeTile<WLOG2>::kEdge;
     uint32_t q = fastdiv(block, p.tiles_a_div);
     const uint32_t ta = block - q * p.tiles_a;
     uint32_t o = fastdiv(q, p.tiles_b_div);
     const uint32_t tb = q - o * p.tiles_b;
     XposeOrigin g;
-    g.a0 = ta * T;
-    g.b0 = tb * T;
+    g.a0 = ta * p.te;
+    g.b0 = tb * p.te;
     g.typed_off = 0;
     g.packed_off = 0;
     for (uint32_t d = 0; d < p.nod; ++d) {
@@ -145,63 +140,61 @@ TP_HD inline XposeOrigin xpose_origin(const XParams& p, uint32_t block) {
     return g;
 }
 
-// Element (a, b) of the tile's outer position, on the typed and on the packed side.
+// Word `w` of element (a, b) of the tile's outer position, on the typed and on the packed side.
 template <int WLOG2>
-TP_HD inline const char* xpose_typed(const XParams& p, const XposeOrigin& g, uint32_t a, uint32_t b) {
-    return p.strided + g.typed_off + static_cast<int64_t>(b) * p.tb_stride + (static_cast<int64_t>(a) << WLOG2);
+TP_HD inline const char* xpose_typed(const XParams& p, const XposeOrigin& g, uint32_t a, uint32_t b, uint32_t w) {
+    return p.strided + g.typed_off + static_cast<int64_t>(b) * p.tb_stride +
+           (static_cast<int64_t>(static_cast<uint64_t>(a) * p.ew + w) << WLOG2);
 }
 template <int WLOG2>
-TP_HD inline char* xpose_packed(const XParams& p, const XposeOrigin& g, uint32_t a, uint32_t b) {
-    return p.packed + g.packed_off + static_cast<int64_t>(a) * p.pa_stride + (static_cast<int64_t>(b) << WLOG2);
+TP_HD inline char* xpose_packed(const XParams& p, const XposeOrigin& g, uint32_t a, uint32_t b, uint32_t w) {
+    return p.packed + g.packed_off + static_cast<int64_t>(a) * p.pa_stride +
+           (static_cast<int64_t>(static_cast<uint64_t>(b) * p.ew + w) << WLOG2);
 }
 
-// Phase 1, thread `tid`: read the tile from the source side, lanes running along the dimension
-// that is contiguous there (A for pack, B for unpack), into lds[b][a] (row pitch kPitch words).
-// All loads are issued before the first LDS write; lanes outside the block re-read the tile's
-// first element, which always exists.
-template <int WLOG2, bool UNPACK, class Mem>
-TP_HD inline void xpose_phase1(const XParams& p, uint32_t block, uint32_t tid, Mem mem,
-                               typename WordOf<WLOG2>::type* lds) {
+// One phase of thread `tid`.  LOAD: read the tile from the source side into LDS; else write it from
+// LDS to the destination side.  Lanes run along the dimension that is contiguous on that side (A
+// on the typed side, B on the packed side), one word each; the tile lives in LDS as
+// lds[b * pitch + a * ew + w].  The second phase may only start when every thread of the workgroup
+// has finished the first.
+template <int WLOG2, bool UNPACK, bool LOAD, class Mem>
+TP_HD inline void xpose_phase(const XParams& p, uint32_t block, uint32_t tid, Mem mem,
+                              typename WordOf<WLOG2>::type* lds) {
     using W = typename WordOf<WLOG2>::type;
     using Tile = XposeTile<WLOG2>;
-    const XposeOrigin g = xpose_origin<WLOG2>(p, block);
-    const uint32_t fast = tid % Tile::kEdge, slow0 = tid / Tile::kEdge;
-    W v[Tile::kPasses];
-    bool ok[Tile::kPasses];
+    const XposeOrigin g = xpose_origin(p, block);
+    const uint32_t fast = tid % Tile::kFast, slow0 = tid / Tile::kFast;
+    const uint32_t fe = p.ew == 1 ? fast : fast / p.ew;  // element and word within it along the fast dimension
+    const uint32_t fw = fast - fe * p.ew;
+    // the typed side is this phase's side when packing and loading, or unpacking and storing
+    constexpr bool kTypedSide = UNPACK != LOAD;
+    if (fe >= p.te) return;
+    // Tile rows in groups of kGroup: all of a group's loads are issued before its first store, so
+    // that many memory accesses are in flight per thread.
+    constexpr uint32_t kGroup = 16;
+    for (uint32_t first = slow0; first < p.te; first += kGroup * Tile::kRowsPerPass) {
+        W v[kGroup];
+        bool ok[kGroup];
+        W* cell[kGroup];
+        char* far[kGroup];
 #pragma unroll
-    for (int k = 0; k < Tile::kPasses; ++k) {
-        const uint32_t slow = slow0 + static_cast<uint32_t>(k) * Tile::kRowsPerPass;
-        const uint32_t a = g.a0 + (UNPACK ? slow : fast), b = g.b0 + (UNPACK ? fast : slow);
-        ok[k] = a < p.ca && b < p.cb;
-        const uint32_t aa = ok[k] ? a : g.a0, bb = ok[k] ? b : g.b0;
-        v[k] = mem.template load<W>(UNPACK ? xpose_packed<WLOG2>(p, g, aa, bb) : xpose_typed<WLOG2>(p, g, aa, bb));
-    }
+        for (uint32_t k = 0; k < kGroup; ++k) {
+            const uint32_t slow = first + k * Tile::kRowsPerPass;
+            const uint32_t la = kTypedSide ? fe : slow, lb = kTypedSide ? slow : fe;
+            const uint32_t a = g.a0 + la, b = g.b0 + lb;
+            ok[k] = slow < p.te && a < p.ca && b < p.cb;
+            // lanes with nothing to move address the tile's first element, which always exists
+            const uint32_t sa = ok[k] ? a : g.a0, sb = ok[k] ? b : g.b0, sw = ok[k] ? fw : 0u;
+            cell[k] = lds + (ok[k] ? lb * p.pitch + la * p.ew + fw : 0u);
+            far[k] = kTypedSide ? const_cast<char*>(xpose_typed<WLOG2>(p, g, sa, sb, sw)) : xpose_packed<WLOG2>(p, g, sa, sb, sw);
+            if (LOAD) v[k] = mem.template load<W>(far[k]);
+            else if (ok[k]) v[k] = *cell[k];
+        }
 #pragma unroll
-    for (int k = 0; k < Tile::kPasses; ++k) {
-        const uint32_t slow = slow0 + static_cast<uint32_t>(k) * Tile::kRowsPerPass;
-        const uint32_t la = UNPACK ? slow : fast, lb = UNPACK ? fast : slow;
-        if (ok[k]) lds[lb * Tile::kPitch + la] = v[k];
-    }
-}
-
-// Phase 2, after every thread of the workgroup has finished phase 1: write the tile to the
-// destination side, lanes running along the dimension that is contiguous there.
-template <int WLOG2, bool UNPACK, class Mem>
-TP_HD inline void xpose_phase2(const XParams& p, uint32_t block, uint32_t tid, Mem mem,
-                               const typename WordOf<WLOG2>::type* lds) {
-    using W = typename WordOf<WLOG2>::type;
-    using Tile = XposeTile<WLOG2>;
-    const XposeOrigin g = xpose_origin<WLOG2>(p, block);
-    const uint32_t fast = tid % Tile::kEdge, slow0 = tid / Tile::kEdge;
-#pragma unroll
-    for (int k = 0; k < Tile::kPasses; ++k) {
-        const uint32_t slow = slow0 + static_cast<uint32_t>(k) * Tile::kRowsPerPass;
-        const uint32_t la = UNPACK ? fast : slow, lb = UNPACK ? slow : fast;
-        const uint32_t a = g.a0 + la, b = g.b0 + lb;
-        if (a < p.ca && b < p.cb) {
-            const W v = lds[lb * Tile::kPitch + la];
-            if (UNPACK) mem.template store<W>(const_cast<char*>(xpose_typed<WLOG2>(p, g, a, b)), v);
-            else mem.template store<W>(xpose_packed<WLOG2>(p, g, a, b), v);
+        for (uint32_t k = 0; k < kGroup; ++k) {
+            if (!ok[k]) continue;
+            if (LOAD) *cell[k] = v[k];
+            else mem.template store<W>(far[k], v[k]);
         }
     }
 }

@@ -75,23 +75,31 @@ struct RunLaunch {
 };
 
 // A transposing launch: per workgroup, every thread's first phase, then every thread's second
-// phase (the barrier), with the workgroup's LDS tile as a host array.
+// phase (the barrier), with the workgroup's LDS tile as a host array.  Reports an LDS index
+// outside the tile as an out-of-bounds access.
 template <int WLOG2, bool UNPACK>
 void run_xpose_words(const tp::Launch& l, HostMem mem) {
     using W = typename tp::WordOf<WLOG2>::type;
     using Tile = tp::XposeTile<WLOG2>;
-    std::vector<W> lds(static_cast<size_t>(Tile::kEdge) * Tile::kPitch);
+    if (static_cast<uint64_t>(l.x.te) * l.x.pitch > static_cast<uint64_t>(Tile::kLdsWords) || l.x.te * l.x.ew > l.x.pitch ||
+        l.x.te * l.x.ew > static_cast<uint32_t>(Tile::kFast)) {
+        mem.c->oob++;
+        return;
+    }
+    std::vector<W> lds(static_cast<size_t>(Tile::kLdsWords));
     for (uint32_t b = 0; b < l.nblocks; ++b) {
         std::memset(lds.data(), 0x5C, lds.size() * sizeof(W));
         for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t)
-            tp::xpose_phase1<WLOG2, UNPACK>(l.x, b, t, mem, lds.data());
+            tp::xpose_phase<WLOG2, UNPACK, true>(l.x, b, t, mem, lds.data());
         for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t)
-            tp::xpose_phase2<WLOG2, UNPACK>(l.x, b, t, mem, lds.data());
+            tp::xpose_phase<WLOG2, UNPACK, false>(l.x, b, t, mem, lds.data());
     }
 }
 
 bool run_xpose(const tp::Launch& l, bool unpack, HostMem mem) {
     switch (l.word_log2) {
+    case 0: unpack ? run_xpose_words<0, true>(l, mem) : run_xpose_words<0, false>(l, mem); return true;
+    case 1: unpack ? run_xpose_words<1, true>(l, mem) : run_xpose_words<1, false>(l, mem); return true;
     case 2: unpack ? run_xpose_words<2, true>(l, mem) : run_xpose_words<2, false>(l, mem); return true;
     case 3: unpack ? run_xpose_words<3, true>(l, mem) : run_xpose_words<3, false>(l, mem); return true;
     case 4: unpack ? run_xpose_words<4, true>(l, mem) : run_xpose_words<4, false>(l, mem); return true;

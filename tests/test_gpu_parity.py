@@ -178,20 +178,25 @@ def test_ragged_runs_at_any_alignment(dev, run):
 
 
 def test_transposing_tiles(dev):
-    # one-word elements adjacent along an outer dimension (a matrix walked column by column): tiles
-    # through LDS, both directions, ragged edges, every word width, outer dimensions, odd addresses
+    # short elements adjacent along an outer dimension (a matrix walked column by column): tiles
+    # through LDS, both directions, ragged edges, every word width, elements of several words,
+    # outer dimensions, odd addresses
     def transposed(m, n, elem, esz, lead=None):
         return hvector(n, 1, esz, vector(m, 1, lead or n, elem))
-    for elem, esz in ((FLOAT, 4), (DOUBLE, 8), (contiguous(16, BYTE), 16)):
-        for m, n, lead in ((64, 64, None), (70, 33, None), (257, 130, 131), (1000, 384, None), (33, 2049, 2050)):
+    for esz, w in ((4, 4), (8, 8), (16, 16), (1, 1), (2, 2), (3, 1), (12, 4), (20, 4), (24, 8), (32, 16)):
+        elem = {4: FLOAT, 8: DOUBLE}.get(esz, contiguous(esz, BYTE))
+        for m, n, lead in ((64, 64, 128), (70, 133, 150), (257, 130, 131), (1000, 384, None), (33, 2049, 2050)):
+            if m * n * esz > (12 << 20):
+                continue
             say("transposing tiles", esz, m, n, lead)
-            plans = roundtrip(transposed(m, n, elem, esz, lead), 1, dev, typed_shift=esz * 3, packed_shift=1,
+            plans = roundtrip(transposed(m, n, elem, esz, lead), 1, dev, typed_shift=esz * 3 + 1, packed_shift=1,
                               position=5, seed=m + n)
-            assert plans["pack"].startswith(f"xpose W={esz} a={n} b={m} ") and plans["unpack"].startswith("xpose"), plans
+            assert plans["pack"].startswith(f"xpose W={w} words={esz // w} ") and f" a={n} b={m} " in plans["pack"], plans
+            assert plans["unpack"].startswith("xpose"), plans
     plans = roundtrip(hvector(3, 1, 300 * 200 * 8 + 24, transposed(300, 200, DOUBLE, 8)), 2, dev, typed_shift=1, seed=7)
-    assert plans["pack"].startswith("xpose W=8 a=200 b=300 outer=2 "), plans
+    assert plans["pack"].startswith("xpose W=8 words=1 tile=64 a=200 b=300 outer=2 "), plans
     plans = roundtrip(hvector(100, 1, 4, hvector(90, 1, -100 * 4, FLOAT)), 3, dev, seed=8)
-    assert plans["pack"].startswith("xpose W=4 a=100 b=90 outer=1 "), plans
+    assert plans["pack"].startswith("xpose W=4 words=1 tile=64 a=100 b=90 outer=1 "), plans
     # the same bytes with the kernel switched off
     try:
         tp.set_override("xpose", 0)

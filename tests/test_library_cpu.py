@@ -376,39 +376,48 @@ def test_emulated_ragged_runs_at_any_alignment():
 
 
 def test_emulated_transposing_tiles():
-    # elements of one word, adjacent in the typed buffer along an outer dimension: tiles through LDS.
-    # Ragged tile edges, every word width, outer dimensions, several objects, a negative stride.
+    # short elements adjacent in the typed buffer along an outer dimension: tiles through LDS.
+    # Ragged tile edges, every word width, elements of several words, outer dimensions, several
+    # objects, a negative stride.
     def transposed(m, n, elem, esz, lead=None):
         """Column-major walk of a row-major m x n matrix of `elem` (leading dimension `lead` elements)."""
         lead = lead or n
         return hvector(n, 1, esz, vector(m, 1, lead, elem))
-    for elem, esz, w in ((FLOAT, 4, 4), (named("DOUBLE"), 8, 8), (contiguous(16, BYTE), 16, 16)):
+    for esz, w, words, tile in ((4, 4, 1, 64), (8, 8, 1, 64), (16, 16, 1, 32), (1, 1, 1, 128), (2, 2, 1, 128), (3, 1, 3, 42),
+                                (12, 4, 3, 21), (24, 8, 3, 21), (32, 16, 2, 16), (20, 4, 5, 12)):
+        elem = {4: FLOAT, 8: named("DOUBLE")}.get(esz, contiguous(esz, BYTE))
         for m, n in ((64, 64), (70, 33), (32, 200), (129, 65)):
-            res = _emulate_roundtrip(transposed(m, n, elem, esz), 1, typed_shift=3, packed_shift=1, position=2)
-            assert res["plan"].startswith(f"xpose W={w} a={n} b={m} outer=0 "), res["plan"]
+            if m * n * esz > 300000:
+                continue
+            lead = max(n, -(-128 // esz))     # rows at least a memory line apart
+            res = _emulate_roundtrip(transposed(m, n, elem, esz, lead), 1, typed_shift=3, packed_shift=1, position=2)
+            assert res["plan"].startswith(f"xpose W={w} words={words} tile={tile} a={n} b={m} outer=0 "), res["plan"]
             assert res["unpack_plan"].startswith(f"xpose W={w} "), res["unpack_plan"]
             assert res["duplicates"] == 0
     # a padded leading dimension, three objects (the count becomes an outer dimension), and a batch of planes
     res = _emulate_roundtrip(transposed(40, 50, FLOAT, 4, lead=61), 3)
-    assert res["plan"].startswith("xpose W=4 a=50 b=40 outer=1 "), res["plan"]
+    assert res["plan"].startswith("xpose W=4 words=1 tile=64 a=50 b=40 outer=1 "), res["plan"]
     planes = hvector(3, 1, 40 * 61 * 4 + 12, transposed(40, 50, FLOAT, 4, lead=61))
     res = _emulate_roundtrip(planes, 2, typed_shift=1)
-    assert res["plan"].startswith("xpose W=4 a=50 b=40 outer=2 "), res["plan"]
-    # an outer dimension nested between the two tiled ones: vector(2 blocks) inside the column walk
+    assert res["plan"].startswith("xpose W=4 words=1 tile=64 a=50 b=40 outer=2 "), res["plan"]
+    # an outer dimension nested between the two tiled ones
     t = hvector(48, 1, 8, hvector(2, 1, 48 * 8 * 40 + 64, vector(40, 1, 48, named("DOUBLE"))))
     res = _emulate_roundtrip(t, 1)
-    assert res["plan"].startswith("xpose W=8 a=48 b=40 outer=1 "), res["plan"]
+    assert res["plan"].startswith("xpose W=8 words=1 tile=64 a=48 b=40 outer=1 "), res["plan"]
     # rows walked backwards (negative stride along B)
     res = _emulate_roundtrip(hvector(36, 1, 4, hvector(45, 1, -36 * 4, FLOAT)), 1)
-    assert res["plan"].startswith("xpose W=4 a=36 b=45 "), res["plan"]
-    # not applicable: short dimensions, elements of several words, B stride below a line, or switched off
-    assert "tile" in _emulate_roundtrip(transposed(20, 64, FLOAT, 4), 1)["plan"]
-    assert "tile" in _emulate_roundtrip(transposed(64, 20, FLOAT, 4), 1)["plan"]
-    assert "tile" in _emulate_roundtrip(hvector(64, 1, 24, vector(64, 1, 64, contiguous(24, BYTE))), 1)["plan"]
-    assert "tile" in _emulate_roundtrip(hvector(8, 1, 4, hvector(64, 1, 32, FLOAT)), 1)["plan"]
-    assert "tile" in _emulate_roundtrip(transposed(64, 64, FLOAT, 4), 1, allow_xpose=False)["plan"]
-    assert "tile" in _emulate_roundtrip(transposed(64, 64, FLOAT, 4), 1, max_word=2)["plan"]
-    assert "tile" in _emulate_roundtrip(transposed(64, 64, FLOAT, 4), 1, max_rows_per_launch=1000)["plan"]
+    assert res["plan"].startswith("xpose W=4 words=1 tile=64 a=36 b=45 "), res["plan"]
+    # a narrower word forced: more words per element
+    res = _emulate_roundtrip(transposed(64, 64, FLOAT, 4), 1, max_word=2)
+    assert res["plan"].startswith("xpose W=2 words=2 tile=64 "), res["plan"]
+    # not applicable: short dimensions, elements of too many words, B stride below a line, or switched off
+    assert "tile W" in _emulate_roundtrip(transposed(20, 64, FLOAT, 4), 1)["plan"]
+    assert "tile W" in _emulate_roundtrip(transposed(64, 20, FLOAT, 4), 1)["plan"]
+    assert "tile W" in _emulate_roundtrip(transposed(64, 64, contiguous(28, BYTE), 28), 1)["plan"]     # 7 words of 4
+    assert "tile W" in _emulate_roundtrip(transposed(64, 64, contiguous(48, BYTE), 48), 1)["plan"]
+    assert "tile W" in _emulate_roundtrip(hvector(8, 1, 4, hvector(64, 1, 32, FLOAT)), 1)["plan"]
+    assert "tile W" in _emulate_roundtrip(transposed(64, 64, FLOAT, 4), 1, allow_xpose=False)["plan"]
+    assert "tile W" in _emulate_roundtrip(transposed(64, 64, FLOAT, 4), 1, max_rows_per_launch=1000)["plan"]
 
 
 def test_emulated_launch_splitting():
