@@ -266,7 +266,7 @@ int tp_resource_stats(int kind, tp_resource_counts *out);
  *   "nt"            "-1" (automatic) or 0..3: streaming hints, bit 0 = non-temporal loads,
  *                   bit 1 = non-temporal stores
  *   "xpose"         "1" (default) or "0": allow the transposing kernel (tiles through LDS for
- *                   blocks whose one-word elements are adjacent along an outer dimension)
+ *                   blocks whose short elements are adjacent along an outer dimension)
  *   "narrow_partial_rows" "1" (default) or "0": unpack rows that are not whole aligned 64-byte
  *                   segments in 4-byte words (measured faster) rather than the widest
  *   "max_rows_per_launch", "max_words_per_run"  1 .. 2^30: split limits (tests lower them to
