@@ -206,6 +206,34 @@ def test_transposing_tiles(dev):
         tp.set_override("xpose", 1)
 
 
+def test_transposed_matrix_full_size(dev):
+    # 4096 x 4096 float64 walked column by column: the packed stream is the transposed matrix
+    # (numpy's transpose is the reference, the C oracle agrees on the leading part), and unpacking it
+    # restores the matrix
+    n = 4096
+    say("full-size transpose: generating")
+    a_h = W.random_grid_f64(4242, (n, n))
+    a = to_dev(a_h.reshape(-1).view(np.uint8), dev)
+    t = hvector(n, 1, 8, vector(n, 1, n, DOUBLE))
+    h = tp.type_from_recipe(t)
+    size = tp.type_size(h)
+    assert size == n * n * 8 and tp.type_get_strided_block(h) == (0, [8, n, n], [1, 8 * n, 8])
+    out = torch.zeros(size + 8, dtype=torch.uint8, device=dev)
+    say("full-size transpose: pack")
+    assert tp.pack(a, 1, h, out, size + 8, 8) == size + 8
+    assert tp.last_plan().startswith("xpose W=8 words=1 tile=64 a=4096 b=4096 outer=0 "), tp.last_plan()
+    got = out.cpu().numpy()
+    assert np.array_equal(got[8:].view(np.float64).reshape(n, n), a_h.T) and not got[:8].any()
+    few = 64 * n * 8   # the first 64 columns through the oracle as well
+    expect = np.zeros(few, np.uint8)
+    cc.pack(a_h.reshape(-1).view(np.uint8), 0, 1, hvector(64, 1, 8, vector(n, 1, n, DOUBLE)), expect, 0)
+    assert np.array_equal(got[8:8 + few], expect)
+    say("full-size transpose: unpack")
+    back = torch.full((n * n * 8,), 0xA5, dtype=torch.uint8, device=dev)
+    assert tp.unpack(out, size + 8, 8, back, 1, h) == size + 8
+    assert torch.equal(back, a)
+
+
 def test_sixteen_dimensions(dev):
     # 15 nested two-element levels and two objects: 16 row dimensions, the most a launch carries
     say("sixteen dimensions")
