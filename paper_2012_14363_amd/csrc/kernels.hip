@@ -68,11 +68,11 @@ __global__ void __launch_bounds__(kBlockThreads) xpose_kernel(const XParams p) {
 
 template <bool UNPACK>
 hipError_t enqueue_xpose(const Launch& l, hipStream_t stream) {
-    // what the kernel's LDS tile assumes of its parameters
-    const uint64_t fast = static_cast<uint64_t>(xpose_fast_words(l.word_log2));
+    // what the kernel's lane mapping and LDS tile assume of their parameters
     const XParams& x = l.x;
-    if (x.ew == 0 || x.te == 0 || uint64_t{x.te} * x.ew > fast || x.pitch < x.te * x.ew ||
-        uint64_t{x.te} * x.pitch > fast * (fast + 32))
+    if (x.ew == 0 || x.te_a == 0 || x.te_b == 0 || x.fa_log2 > 8 || x.fb_log2 > 8 ||
+        uint64_t{x.te_a} * x.ew > (uint64_t{1} << x.fa_log2) || uint64_t{x.te_b} * x.ew > (uint64_t{1} << x.fb_log2) ||
+        x.pitch < x.te_a * x.ew || uint64_t{x.te_b} * x.pitch > static_cast<uint64_t>(xpose_lds_words(l.word_log2)))
         return hipErrorInvalidValue;
     const dim3 grid(l.nblocks), block(kBlockThreads);
     switch (l.word_log2) {

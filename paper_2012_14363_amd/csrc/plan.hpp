@@ -45,7 +45,7 @@ struct KParams {
 // Parameters of the transposing kernel, for blocks whose elements (short runs of `ew` words of W
 // bytes) are adjacent in the typed buffer along one row dimension ("A") while the packed stream
 // runs along another ("B", the innermost row dimension): a plain row-by-row copy would touch one
-// memory line per element on one side or the other.  Workgroups move `te` x `te` element tiles
+// memory line per element on one side or the other.  Workgroups move te_a x te_b element tiles
 // through LDS instead, reading along the dimension that is contiguous on the source side and
 // writing along the one that is contiguous on the destination side.  This is where the stride
 // order the paper's canonicalizer sorts by (Sec. 3.2, last pass) matters; the packed order itself
@@ -55,7 +55,8 @@ struct XParams {
     char* packed = nullptr;         // contiguous buffer + position
     uint32_t ca = 0, cb = 0;        // element counts of the two tiled dimensions
     uint32_t ew = 1;                // words per element (element = ew << word_log2 bytes)
-    uint32_t te = 0;                // tile edge in elements: te * ew words fit one tile row
+    uint32_t te_a = 0, te_b = 0;    // tile edges in elements (a thin dimension is covered whole, the other grows)
+    uint32_t fa_log2 = 0, fb_log2 = 0;  // lanes along a tile row on the typed (A) and packed (B) side: >= te * ew
     uint32_t pitch = 0;             // LDS row pitch in words (chosen so that column accesses spread over banks)
     int64_t tb_stride = 0;          // typed bytes between B-neighbours (A-neighbours are one element apart)
     int64_t pa_stride = 0;          // packed bytes between A-neighbours (B-neighbours are one element apart)
@@ -68,10 +69,10 @@ struct XParams {
     int64_t opstride[kMaxDims] = {};  // packed bytes per step
 };
 
-// Words along one tile row of the transposing kernel, by word width: a tile row is 128 bytes to
-// 1 KiB of contiguous memory, and the LDS tile (kXposeFast rows of at most kXposeFast + 32 words)
-// stays below 50 KiB.
+// Words along one row of a square tile of the transposing kernel, by word width: a tile row is
+// 128 bytes to 1 KiB of contiguous memory.  The LDS tile holds xpose_lds_words() words (below 50 KiB).
 constexpr int xpose_fast_words(int word_log2) { return word_log2 == 4 ? 32 : word_log2 >= 2 ? 64 : 128; }
+constexpr int xpose_lds_words(int word_log2) { return xpose_fast_words(word_log2) * (xpose_fast_words(word_log2) + 32); }
 
 enum LaunchKind : int { kTile = 0, kXpose = 1 };
 

@@ -108,9 +108,7 @@ TP_HD inline void tile_thread(const P& p, uint32_t block, uint32_t tid, Mem mem)
 // ------------------------------------------------------------------ transposing tiles
 template <int WLOG2>
 struct XposeTile {
-    static constexpr int kFast = xpose_fast_words(WLOG2);  // lanes (words) along a tile row
-    static constexpr int kRowsPerPass = kBlockThreads / kFast;
-    static constexpr int kLdsWords = kFast * (kFast + 32);  // te rows of `pitch` words at most
+    static constexpr int kLdsWords = xpose_lds_words(WLOG2);  // te_b rows of `pitch` words at most
 };
 
 // Where workgroup `block` works: its tile's first element along A and B and the byte offsets of
@@ -126,8 +124,8 @@ TP_HD inline XposeOrigin xpose_origin(const XParams& p, uint32_t block) {
     uint32_t o = fastdiv(q, p.tiles_b_div);
     const uint32_t tb = q - o * p.tiles_b;
     XposeOrigin g;
-    g.a0 = ta * p.te;
-    g.b0 = tb * p.te;
+    g.a0 = ta * p.te_a;
+    g.b0 = tb * p.te_b;
     g.typed_off = 0;
     g.packed_off = 0;
     for (uint32_t d = 0; d < p.nod; ++d) {
@@ -161,28 +159,30 @@ template <int WLOG2, bool UNPACK, bool LOAD, class Mem>
 TP_HD inline void xpose_phase(const XParams& p, uint32_t block, uint32_t tid, Mem mem,
                               typename WordOf<WLOG2>::type* lds) {
     using W = typename WordOf<WLOG2>::type;
-    using Tile = XposeTile<WLOG2>;
     const XposeOrigin g = xpose_origin(p, block);
-    const uint32_t fast = tid % Tile::kFast, slow0 = tid / Tile::kFast;
-    const uint32_t fe = p.ew == 1 ? fast : fast / p.ew;  // element and word within it along the fast dimension
-    const uint32_t fw = fast - fe * p.ew;
     // the typed side is this phase's side when packing and loading, or unpacking and storing
     constexpr bool kTypedSide = UNPACK != LOAD;
-    if (fe >= p.te) return;
+    const uint32_t f_log2 = kTypedSide ? p.fa_log2 : p.fb_log2;
+    const uint32_t te_fast = kTypedSide ? p.te_a : p.te_b, te_slow = kTypedSide ? p.te_b : p.te_a;
+    const uint32_t rows_per_pass = static_cast<uint32_t>(kBlockThreads) >> f_log2;
+    const uint32_t fast = tid & ((1u << f_log2) - 1u), slow0 = tid >> f_log2;
+    const uint32_t fe = p.ew == 1 ? fast : fast / p.ew;  // element and word within it along the fast dimension
+    const uint32_t fw = fast - fe * p.ew;
+    if (fe >= te_fast) return;
     // Tile rows in groups of kGroup: all of a group's loads are issued before its first store, so
     // that many memory accesses are in flight per thread.
     constexpr uint32_t kGroup = 16;
-    for (uint32_t first = slow0; first < p.te; first += kGroup * Tile::kRowsPerPass) {
+    for (uint32_t first = slow0; first < te_slow; first += kGroup * rows_per_pass) {
         W v[kGroup];
         bool ok[kGroup];
         W* cell[kGroup];
         char* far[kGroup];
 #pragma unroll
         for (uint32_t k = 0; k < kGroup; ++k) {
-            const uint32_t slow = first + k * Tile::kRowsPerPass;
+            const uint32_t slow = first + k * rows_per_pass;
             const uint32_t la = kTypedSide ? fe : slow, lb = kTypedSide ? slow : fe;
             const uint32_t a = g.a0 + la, b = g.b0 + lb;
-            ok[k] = slow < p.te && a < p.ca && b < p.cb;
+            ok[k] = slow < te_slow && a < p.ca && b < p.cb;
             // lanes with nothing to move address the tile's first element, which always exists
             const uint32_t sa = ok[k] ? a : g.a0, sb = ok[k] ? b : g.b0, sw = ok[k] ? fw : 0u;
             cell[k] = lds + (ok[k] ? lb * p.pitch + la * p.ew + fw : 0u);

@@ -194,9 +194,17 @@ def test_transposing_tiles(dev):
             assert plans["pack"].startswith(f"xpose W={w} words={esz // w} ") and f" a={n} b={m} " in plans["pack"], plans
             assert plans["unpack"].startswith("xpose"), plans
     plans = roundtrip(hvector(3, 1, 300 * 200 * 8 + 24, transposed(300, 200, DOUBLE, 8)), 2, dev, typed_shift=1, seed=7)
-    assert plans["pack"].startswith("xpose W=8 words=1 tile=64 a=200 b=300 outer=2 "), plans
+    assert plans["pack"].startswith("xpose W=8 words=1 tile=64x64 a=200 b=300 outer=2 "), plans
     plans = roundtrip(hvector(100, 1, 4, hvector(90, 1, -100 * 4, FLOAT)), 3, dev, seed=8)
-    assert plans["pack"].startswith("xpose W=4 words=1 tile=64 a=100 b=90 outer=1 "), plans
+    assert plans["pack"].startswith("xpose W=4 words=1 tile=64x64 a=100 b=90 outer=1 "), plans
+    # thin matrices: an array of records turned into one array per field, and back
+    for f in (4, 6, 8, 16, 31):
+        say("thin transposes, fields", f)
+        plans = roundtrip(hvector(f, 1, 8, vector(100003, 1, f, DOUBLE)), 1, dev, typed_shift=1, packed_shift=3, seed=f)
+        assert plans["unpack"].startswith(f"xpose W=8 words=1 tile={f}x186 "), plans
+        assert plans["pack"].startswith("xpose" if f >= 6 else "tile W"), plans
+        plans = roundtrip(hvector(50021, 1, 4, vector(f, 1, 50021 + 7, FLOAT)), 2, dev, typed_shift=4, position=1, seed=f)
+        assert plans["unpack"].startswith("xpose W=4 words=1 tile=") and f"x{f} a=50021 b={f} outer=1 " in plans["unpack"], plans
     # the same bytes with the kernel switched off
     try:
         tp.set_override("xpose", 0)
@@ -221,7 +229,7 @@ def test_transposed_matrix_full_size(dev):
     out = torch.zeros(size + 8, dtype=torch.uint8, device=dev)
     say("full-size transpose: pack")
     assert tp.pack(a, 1, h, out, size + 8, 8) == size + 8
-    assert tp.last_plan().startswith("xpose W=8 words=1 tile=64 a=4096 b=4096 outer=0 "), tp.last_plan()
+    assert tp.last_plan().startswith("xpose W=8 words=1 tile=64x64 a=4096 b=4096 outer=0 "), tp.last_plan()
     got = out.cpu().numpy()
     assert np.array_equal(got[8:].view(np.float64).reshape(n, n), a_h.T) and not got[:8].any()
     few = 64 * n * 8   # the first 64 columns through the oracle as well

@@ -391,31 +391,48 @@ def test_emulated_transposing_tiles():
                 continue
             lead = max(n, -(-128 // esz))     # rows at least a memory line apart
             res = _emulate_roundtrip(transposed(m, n, elem, esz, lead), 1, typed_shift=3, packed_shift=1, position=2)
-            assert res["plan"].startswith(f"xpose W={w} words={words} tile={tile} a={n} b={m} outer=0 "), res["plan"]
+            ta, tb = min(tile, n), min(tile, m)
+            if 2 * ta > tile and 2 * tb > tile:     # neither dimension thin: square tiles (cut at the matrix edge)
+                assert res["plan"].startswith(f"xpose W={w} words={words} tile={ta}x{tb} a={n} b={m} outer=0 "), res["plan"]
+            assert res["plan"].startswith(f"xpose W={w} words={words} tile="), res["plan"]
             assert res["unpack_plan"].startswith(f"xpose W={w} "), res["unpack_plan"]
             assert res["duplicates"] == 0
     # a padded leading dimension, three objects (the count becomes an outer dimension), and a batch of planes
     res = _emulate_roundtrip(transposed(40, 50, FLOAT, 4, lead=61), 3)
-    assert res["plan"].startswith("xpose W=4 words=1 tile=64 a=50 b=40 outer=1 "), res["plan"]
+    assert res["plan"].startswith("xpose W=4 words=1 tile=50x40 a=50 b=40 outer=1 "), res["plan"]
     planes = hvector(3, 1, 40 * 61 * 4 + 12, transposed(40, 50, FLOAT, 4, lead=61))
     res = _emulate_roundtrip(planes, 2, typed_shift=1)
-    assert res["plan"].startswith("xpose W=4 words=1 tile=64 a=50 b=40 outer=2 "), res["plan"]
+    assert res["plan"].startswith("xpose W=4 words=1 tile=50x40 a=50 b=40 outer=2 "), res["plan"]
     # an outer dimension nested between the two tiled ones
     t = hvector(48, 1, 8, hvector(2, 1, 48 * 8 * 40 + 64, vector(40, 1, 48, named("DOUBLE"))))
     res = _emulate_roundtrip(t, 1)
-    assert res["plan"].startswith("xpose W=8 words=1 tile=64 a=48 b=40 outer=1 "), res["plan"]
+    assert res["plan"].startswith("xpose W=8 words=1 tile=48x40 a=48 b=40 outer=1 "), res["plan"]
     # rows walked backwards (negative stride along B)
     res = _emulate_roundtrip(hvector(36, 1, 4, hvector(45, 1, -36 * 4, FLOAT)), 1)
-    assert res["plan"].startswith("xpose W=4 words=1 tile=64 a=36 b=45 "), res["plan"]
+    assert res["plan"].startswith("xpose W=4 words=1 tile=36x45 a=36 b=45 "), res["plan"]
     # a narrower word forced: more words per element
     res = _emulate_roundtrip(transposed(64, 64, FLOAT, 4), 1, max_word=2)
-    assert res["plan"].startswith("xpose W=2 words=2 tile=64 "), res["plan"]
-    # not applicable: short dimensions, elements of too many words, B stride below a line, or switched off
-    assert "tile W" in _emulate_roundtrip(transposed(20, 64, FLOAT, 4), 1)["plan"]
-    assert "tile W" in _emulate_roundtrip(transposed(64, 20, FLOAT, 4), 1)["plan"]
+    assert res["plan"].startswith("xpose W=2 words=2 tile=64x64 "), res["plan"]
+    # thin matrices (records of a few fields turned into one array per field, and back): the short
+    # dimension is covered whole and the tile grows along the other
+    rec = lambda f, n: hvector(f, 1, 8, vector(n, 1, f, named("DOUBLE")))      # noqa: E731  array of records -> field arrays
+    fld = lambda f, n: hvector(n, 1, 8, vector(f, 1, n + 5, named("DOUBLE")))  # noqa: E731  field arrays -> array of records
+    for f in (6, 8, 16, 31):
+        res = _emulate_roundtrip(rec(f, 700), 1, typed_shift=1)
+        assert res["plan"].startswith(f"xpose W=8 words=1 tile={f}x186 a={f} b=700 "), res["plan"]
+        res = _emulate_roundtrip(fld(f, 700), 2, packed_shift=3)
+        assert res["plan"].startswith(f"xpose W=8 words=1 tile={min(256, 6144 // f - 32)}x{f} a=700 b={f} outer=1 "), res["plan"]
+    assert "xpose W=1 words=3 tile=7x85 " in _emulate_roundtrip(hvector(7, 1, 3, vector(900, 1, 7, contiguous(3, BYTE))), 1)["plan"]
+    # records of very few fields keep the row-by-row kernel for pack, and below four fields for unpack too
+    res = _emulate_roundtrip(rec(4, 700), 1)
+    assert "tile W" in res["plan"] and "xpose" in res["unpack_plan"]
+    res = _emulate_roundtrip(rec(3, 700), 1)
+    assert "tile W" in res["plan"] and "tile W" in res["unpack_plan"]
+    # not applicable: too few elements, elements of too many words, B stride below two elements, or switched off
+    assert "tile W" in _emulate_roundtrip(transposed(20, 40, FLOAT, 4), 1)["plan"]
     assert "tile W" in _emulate_roundtrip(transposed(64, 64, contiguous(28, BYTE), 28), 1)["plan"]     # 7 words of 4
     assert "tile W" in _emulate_roundtrip(transposed(64, 64, contiguous(48, BYTE), 48), 1)["plan"]
-    assert "tile W" in _emulate_roundtrip(hvector(8, 1, 4, hvector(64, 1, 32, FLOAT)), 1)["plan"]
+    assert "tile W" in _emulate_roundtrip(hvector(64, 1, 8, hvector(64, 1, 12, contiguous(8, BYTE))), 1)["plan"]   # overlapping rows
     assert "tile W" in _emulate_roundtrip(transposed(64, 64, FLOAT, 4), 1, allow_xpose=False)["plan"]
     assert "tile W" in _emulate_roundtrip(transposed(64, 64, FLOAT, 4), 1, max_rows_per_launch=1000)["plan"]
 
