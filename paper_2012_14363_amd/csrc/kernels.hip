@@ -57,13 +57,20 @@ __global__ void __launch_bounds__(kBlockThreads) tile_kernel(const KParams p) {
 }
 
 // Transposing tiles through LDS (tile_body.hpp: xpose_phase).
-template <int WLOG2, bool UNPACK>
+template <int WLOG2, bool UNPACK, bool SQUARE>
 __global__ void __launch_bounds__(kBlockThreads) xpose_kernel(const XParams p) {
     using W = typename WordOf<WLOG2>::type;
     __shared__ W lds[XposeTile<WLOG2>::kLdsWords];
-    xpose_phase<WLOG2, UNPACK, true>(p, blockIdx.x, threadIdx.x, DeviceMem<3>{}, lds);
+    xpose_phase<WLOG2, UNPACK, true, SQUARE>(p, blockIdx.x, threadIdx.x, DeviceMem<3>{}, lds);
     __syncthreads();
-    xpose_phase<WLOG2, UNPACK, false>(p, blockIdx.x, threadIdx.x, DeviceMem<3>{}, lds);
+    xpose_phase<WLOG2, UNPACK, false, SQUARE>(p, blockIdx.x, threadIdx.x, DeviceMem<3>{}, lds);
+}
+
+template <int WLOG2, bool UNPACK>
+void launch_xpose(const Launch& l, hipStream_t stream) {
+    const dim3 grid(l.nblocks), block(kBlockThreads);
+    if (xpose_is_square(l.x, WLOG2)) hipLaunchKernelGGL((xpose_kernel<WLOG2, UNPACK, true>), grid, block, 0, stream, l.x);
+    else hipLaunchKernelGGL((xpose_kernel<WLOG2, UNPACK, false>), grid, block, 0, stream, l.x);
 }
 
 template <bool UNPACK>
@@ -74,13 +81,12 @@ hipError_t enqueue_xpose(const Launch& l, hipStream_t stream) {
         uint64_t{x.te_a} * x.ew > (uint64_t{1} << x.fa_log2) || uint64_t{x.te_b} * x.ew > (uint64_t{1} << x.fb_log2) ||
         x.pitch < x.te_a * x.ew || uint64_t{x.te_b} * x.pitch > static_cast<uint64_t>(xpose_lds_words(l.word_log2)))
         return hipErrorInvalidValue;
-    const dim3 grid(l.nblocks), block(kBlockThreads);
     switch (l.word_log2) {
-    case 0: hipLaunchKernelGGL((xpose_kernel<0, UNPACK>), grid, block, 0, stream, l.x); break;
-    case 1: hipLaunchKernelGGL((xpose_kernel<1, UNPACK>), grid, block, 0, stream, l.x); break;
-    case 2: hipLaunchKernelGGL((xpose_kernel<2, UNPACK>), grid, block, 0, stream, l.x); break;
-    case 3: hipLaunchKernelGGL((xpose_kernel<3, UNPACK>), grid, block, 0, stream, l.x); break;
-    case 4: hipLaunchKernelGGL((xpose_kernel<4, UNPACK>), grid, block, 0, stream, l.x); break;
+    case 0: launch_xpose<0, UNPACK>(l, stream); break;
+    case 1: launch_xpose<1, UNPACK>(l, stream); break;
+    case 2: launch_xpose<2, UNPACK>(l, stream); break;
+    case 3: launch_xpose<3, UNPACK>(l, stream); break;
+    case 4: launch_xpose<4, UNPACK>(l, stream); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

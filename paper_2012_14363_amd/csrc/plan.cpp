@@ -144,12 +144,18 @@ struct Splitter {
 bool plan_xpose(const PlanInput& in, const std::vector<Dim>& dims, const char* typed, std::vector<Launch>* out) {
     if (!in.allow_xpose || dims.size() < 3) return false;
     const int64_t run = dims[0].count;
-    // Elements beyond 32 bytes leave tiles of too few elements: measured slower than the
-    // row-by-row kernel (64-byte elements: 258 us against 124 for a 2048 x 2048 pack).
-    if (run > 32) return false;
+    if (run > 64) return false;
     const int word_log2 = std::min({4, in.max_word_log2, __builtin_ctzll(static_cast<uint64_t>(run))});
     const int64_t ew = run >> word_log2;
-    const int64_t square = xpose_fast_words(word_log2) / ew;  // edge of a square tile, in elements
+    // Edge of a square tile, in elements: one-word elements use the power of two the kernel's
+    // constant-parameter variant is built for; elements of several words take the largest edge
+    // whose rows fit the workgroup (256 words) and whose tile fits LDS.
+    const int64_t lds_words = xpose_lds_words(word_log2);
+    int64_t square = xpose_fast_words(word_log2);
+    if (ew > 1) {
+        square = kBlockThreads / ew;
+        while (square > 0 && square * (square * ew + 32) > lds_words) --square;
+    }
     if (square < 12) return false;
     // tests that lower the split limits mean the row-by-row kernel
     if (in.max_rows_per_launch != (int64_t{1} << 30) || in.max_words_per_run != (int64_t{1} << 30)) return false;
@@ -174,7 +180,6 @@ bool plan_xpose(const PlanInput& in, const std::vector<Dim>& dims, const char* t
     int64_t te_a = std::min<int64_t>(square, dims[a].count), te_b = std::min<int64_t>(square, b.count);
     uint32_t pitch = static_cast<uint32_t>(te_a * ew);
     while (pitch % 32 != static_cast<uint32_t>(ew % 32)) ++pitch;
-    const int64_t lds_words = xpose_lds_words(word_log2);
     if (te_a * 2 <= square) te_b = std::min({b.count, int64_t{kBlockThreads} / ew, lds_words / pitch});
     else if (te_b * 2 <= square) {
         te_a = std::min({dims[a].count, int64_t{kBlockThreads} / ew, (lds_words / te_b - 32) / ew});

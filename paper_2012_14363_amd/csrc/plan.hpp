@@ -72,6 +72,11 @@ struct XParams {
 // Words along one row of a square tile of the transposing kernel, by word width: a tile row is
 // 128 bytes to 1 KiB of contiguous memory.  The LDS tile holds xpose_lds_words() words (below 50 KiB).
 constexpr int xpose_fast_words(int word_log2) { return word_log2 == 4 ? 32 : word_log2 >= 2 ? 64 : 128; }
+// True if a launch has the shape the kernel's constant-parameter variant assumes.
+inline bool xpose_is_square(const XParams& x, int word_log2) {
+    const uint32_t edge = static_cast<uint32_t>(word_log2 == 4 ? 32 : word_log2 >= 2 ? 64 : 128);
+    return x.ew == 1 && x.te_a == edge && x.te_b == edge && x.pitch == edge + 1;
+}
 constexpr int xpose_lds_words(int word_log2) { return xpose_fast_words(word_log2) * (xpose_fast_words(word_log2) + 32); }
 
 enum LaunchKind : int { kTile = 0, kXpose = 1 };

@@ -155,19 +155,25 @@ TP_HD inline char* xpose_packed(const XParams& p, const XposeOrigin& g, uint32_t
 // on the typed side, B on the packed side), one word each; the tile lives in LDS as
 // lds[b * pitch + a * ew + w].  The second phase may only start when every thread of the workgroup
 // has finished the first.
-template <int WLOG2, bool UNPACK, bool LOAD, class Mem>
+// SQUARE: the common case of one-word elements in full square tiles (te_a == te_b ==
+// xpose_fast_words, pitch one more), with those parameters as compile-time constants.
+template <int WLOG2, bool UNPACK, bool LOAD, bool SQUARE, class Mem>
 TP_HD inline void xpose_phase(const XParams& p, uint32_t block, uint32_t tid, Mem mem,
                               typename WordOf<WLOG2>::type* lds) {
     using W = typename WordOf<WLOG2>::type;
     const XposeOrigin g = xpose_origin(p, block);
     // the typed side is this phase's side when packing and loading, or unpacking and storing
     constexpr bool kTypedSide = UNPACK != LOAD;
-    const uint32_t f_log2 = kTypedSide ? p.fa_log2 : p.fb_log2;
-    const uint32_t te_fast = kTypedSide ? p.te_a : p.te_b, te_slow = kTypedSide ? p.te_b : p.te_a;
+    constexpr uint32_t kEdge = static_cast<uint32_t>(xpose_fast_words(WLOG2));
+    constexpr uint32_t kEdgeLog2 = kEdge == 32 ? 5u : kEdge == 64 ? 6u : 7u;
+    const uint32_t ew = SQUARE ? 1u : p.ew, pitch = SQUARE ? kEdge + 1u : p.pitch;
+    const uint32_t f_log2 = SQUARE ? kEdgeLog2 : kTypedSide ? p.fa_log2 : p.fb_log2;
+    const uint32_t te_fast = SQUARE ? kEdge : kTypedSide ? p.te_a : p.te_b;
+    const uint32_t te_slow = SQUARE ? kEdge : kTypedSide ? p.te_b : p.te_a;
     const uint32_t rows_per_pass = static_cast<uint32_t>(kBlockThreads) >> f_log2;
     const uint32_t fast = tid & ((1u << f_log2) - 1u), slow0 = tid >> f_log2;
-    const uint32_t fe = p.ew == 1 ? fast : fast / p.ew;  // element and word within it along the fast dimension
-    const uint32_t fw = fast - fe * p.ew;
+    const uint32_t fe = ew == 1 ? fast : fast / ew;  // element and word within it along the fast dimension
+    const uint32_t fw = fast - fe * ew;
     if (fe >= te_fast) return;
     // Tile rows in groups of kGroup: all of a group's loads are issued before its first store, so
     // that many memory accesses are in flight per thread.
@@ -185,7 +191,7 @@ TP_HD inline void xpose_phase(const XParams& p, uint32_t block, uint32_t tid, Me
             ok[k] = slow < te_slow && a < p.ca && b < p.cb;
             // lanes with nothing to move address the tile's first element, which always exists
             const uint32_t sa = ok[k] ? a : g.a0, sb = ok[k] ? b : g.b0, sw = ok[k] ? fw : 0u;
-            cell[k] = lds + (ok[k] ? lb * p.pitch + la * p.ew + fw : 0u);
+            cell[k] = lds + (ok[k] ? lb * pitch + la * ew + fw : 0u);
             far[k] = kTypedSide ? const_cast<char*>(xpose_typed<WLOG2>(p, g, sa, sb, sw)) : xpose_packed<WLOG2>(p, g, sa, sb, sw);
             if (LOAD) v[k] = mem.template load<W>(far[k]);
             else if (ok[k]) v[k] = *cell[k];

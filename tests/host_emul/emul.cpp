@@ -91,10 +91,16 @@ void run_xpose_words(const tp::Launch& l, HostMem mem) {
     std::vector<W> lds(static_cast<size_t>(Tile::kLdsWords));
     for (uint32_t b = 0; b < l.nblocks; ++b) {
         std::memset(lds.data(), 0x5C, lds.size() * sizeof(W));
-        for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t)
-            tp::xpose_phase<WLOG2, UNPACK, true>(l.x, b, t, mem, lds.data());
-        for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t)
-            tp::xpose_phase<WLOG2, UNPACK, false>(l.x, b, t, mem, lds.data());
+        // the same choice of variant as the device launcher's
+        const bool square = tp::xpose_is_square(l.x, WLOG2);
+        for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t) {
+            if (square) tp::xpose_phase<WLOG2, UNPACK, true, true>(l.x, b, t, mem, lds.data());
+            else tp::xpose_phase<WLOG2, UNPACK, true, false>(l.x, b, t, mem, lds.data());
+        }
+        for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t) {
+            if (square) tp::xpose_phase<WLOG2, UNPACK, false, true>(l.x, b, t, mem, lds.data());
+            else tp::xpose_phase<WLOG2, UNPACK, false, false>(l.x, b, t, mem, lds.data());
+        }
     }
 }
 

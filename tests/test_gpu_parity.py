@@ -183,7 +183,7 @@ def test_transposing_tiles(dev):
     # outer dimensions, odd addresses
     def transposed(m, n, elem, esz, lead=None):
         return hvector(n, 1, esz, vector(m, 1, lead or n, elem))
-    for esz, w in ((4, 4), (8, 8), (16, 16), (1, 1), (2, 2), (3, 1), (12, 4), (20, 4), (24, 8), (32, 16)):
+    for esz, w in ((4, 4), (8, 8), (16, 16), (1, 1), (2, 2), (3, 1), (12, 4), (20, 4), (24, 8), (32, 16), (48, 16), (64, 16)):
         elem = {4: FLOAT, 8: DOUBLE}.get(esz, contiguous(esz, BYTE))
         for m, n, lead in ((64, 64, 128), (70, 133, 150), (257, 130, 131), (1000, 384, None), (33, 2049, 2050)):
             if m * n * esz > (12 << 20):

@@ -383,8 +383,8 @@ def test_emulated_transposing_tiles():
         """Column-major walk of a row-major m x n matrix of `elem` (leading dimension `lead` elements)."""
         lead = lead or n
         return hvector(n, 1, esz, vector(m, 1, lead, elem))
-    for esz, w, words, tile in ((4, 4, 1, 64), (8, 8, 1, 64), (16, 16, 1, 32), (1, 1, 1, 128), (2, 2, 1, 128), (3, 1, 3, 42),
-                                (12, 4, 3, 21), (24, 8, 3, 21), (32, 16, 2, 16), (20, 4, 5, 12)):
+    for esz, w, words, tile in ((4, 4, 1, 64), (8, 8, 1, 64), (16, 16, 1, 32), (1, 1, 1, 128), (2, 2, 1, 128), (3, 1, 3, 77),
+                                (12, 4, 3, 40), (24, 8, 3, 40), (32, 16, 2, 24), (20, 4, 5, 32), (28, 4, 7, 27), (48, 16, 3, 21), (64, 16, 4, 18)):
         elem = {4: FLOAT, 8: named("DOUBLE")}.get(esz, contiguous(esz, BYTE))
         for m, n in ((64, 64), (70, 33), (32, 200), (129, 65)):
             if m * n * esz > 300000:
@@ -430,8 +430,8 @@ def test_emulated_transposing_tiles():
     assert "tile W" in res["plan"] and "tile W" in res["unpack_plan"]
     # not applicable: too few elements, elements of too many words, B stride below two elements, or switched off
     assert "tile W" in _emulate_roundtrip(transposed(20, 40, FLOAT, 4), 1)["plan"]
-    assert "tile W" in _emulate_roundtrip(transposed(64, 64, contiguous(28, BYTE), 28), 1)["plan"]     # 7 words of 4
-    assert "tile W" in _emulate_roundtrip(transposed(64, 64, contiguous(48, BYTE), 48), 1)["plan"]
+    assert "tile W" in _emulate_roundtrip(transposed(64, 64, contiguous(31, BYTE), 31), 1)["plan"]     # 31 words of 1
+    assert "tile W" in _emulate_roundtrip(transposed(64, 64, contiguous(80, BYTE), 80), 1)["plan"]
     assert "tile W" in _emulate_roundtrip(hvector(64, 1, 8, hvector(64, 1, 12, contiguous(8, BYTE))), 1)["plan"]   # overlapping rows
     assert "tile W" in _emulate_roundtrip(transposed(64, 64, FLOAT, 4), 1, allow_xpose=False)["plan"]
     assert "tile W" in _emulate_roundtrip(transposed(64, 64, FLOAT, 4), 1, max_rows_per_launch=1000)["plan"]
