@@ -164,12 +164,12 @@ bool plan_xpose(const PlanInput& in, const std::vector<Dim>& dims, const char* t
     for (size_t d = 2; d < dims.size() && a == 0; ++d)
         if (dims[d].stride == run && dims[d].count >= 2) a = d;
     if (a == 0) return false;
-    // A dimension of very few elements (records of three or four fields): the row-by-row kernel's
-    // re-reads mostly hit in cache and it measured as fast or faster (three fields of 8 bytes, 96 MiB:
-    // pack 73 us against 111, unpack 119 against 110; four fields: unpack 224 against 111; eight
-    // fields: 376 against 132 and 876 against 125).
+    // A dimension of very few elements (records of two or three fields): the row-by-row kernel's
+    // re-reads mostly hit in cache, and tiles that thin give a workgroup little to do.  Measured on
+    // 4 Mi records of 8-byte fields, row by row against transposing, pack / unpack in us: three fields
+    // 72 / 120 against 84 / 87, four fields 110 / 224 against 86 / 89, eight 376 / 876 against 108 / 111.
     const int64_t thin = std::min(dims[a].count, b.count);
-    if (thin < (in.unpack ? 4 : 6)) return false;
+    if (thin < (in.unpack ? 3 : 4)) return false;
     // Walking B row by row uses one element of every |stride| bytes and comes back for the rest
     // on later rows: worth transposing from an amplification of two, given enough elements.
     const int64_t bstep = b.stride < 0 ? -b.stride : b.stride;
@@ -178,14 +178,21 @@ bool plan_xpose(const PlanInput& in, const std::vector<Dim>& dims, const char* t
     // Tile shape: square where both dimensions are long; a dimension shorter than half an edge is
     // covered whole and the other edge grows (to 256 words per row, as far as LDS reaches).
     int64_t te_a = std::min<int64_t>(square, dims[a].count), te_b = std::min<int64_t>(square, b.count);
-    uint32_t pitch = static_cast<uint32_t>(te_a * ew);
-    while (pitch % 32 != static_cast<uint32_t>(ew % 32)) ++pitch;
+    // LDS row pitch in words: at least a tile row, and such that lanes walking down a tile
+    // column fall into distinct banks (32 of them): any odd pitch for one-word elements, a pitch
+    // congruent to ew modulo 32 for elements of ew words.
+    auto pitch_for = [ew](int64_t edge_a) {
+        uint32_t pitch = static_cast<uint32_t>(edge_a * ew);
+        if (ew == 1) return pitch | 1u;
+        while (pitch % 32 != static_cast<uint32_t>(ew % 32)) ++pitch;
+        return pitch;
+    };
+    uint32_t pitch = pitch_for(te_a);
     if (te_a * 2 <= square) te_b = std::min({b.count, int64_t{kBlockThreads} / ew, lds_words / pitch});
     else if (te_b * 2 <= square) {
         te_a = std::min({dims[a].count, int64_t{kBlockThreads} / ew, (lds_words / te_b - 32) / ew});
         if (te_a < 1) return false;
-        pitch = static_cast<uint32_t>(te_a * ew);
-        while (pitch % 32 != static_cast<uint32_t>(ew % 32)) ++pitch;
+        pitch = pitch_for(te_a);
     }
     if (te_b * pitch > lds_words) return false;
 
@@ -203,8 +210,6 @@ bool plan_xpose(const PlanInput& in, const std::vector<Dim>& dims, const char* t
     x.te_b = static_cast<uint32_t>(te_b);
     x.fa_log2 = static_cast<uint32_t>(ceil_log2(static_cast<uint64_t>(te_a * ew)));
     x.fb_log2 = static_cast<uint32_t>(ceil_log2(static_cast<uint64_t>(te_b * ew)));
-    // LDS row pitch: at least a tile row, and congruent to ew modulo the 32 banks, so that lanes
-    // walking down a tile column (ew consecutive words per element) fall into distinct banks
     x.pitch = pitch;
     x.tb_stride = b.stride;
     x.tiles_a = static_cast<uint32_t>((dims[a].count + te_a - 1) / te_a);

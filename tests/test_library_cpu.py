@@ -419,14 +419,16 @@ def test_emulated_transposing_tiles():
     fld = lambda f, n: hvector(n, 1, 8, vector(f, 1, n + 5, named("DOUBLE")))  # noqa: E731  field arrays -> array of records
     for f in (6, 8, 16, 31):
         res = _emulate_roundtrip(rec(f, 700), 1, typed_shift=1)
-        assert res["plan"].startswith(f"xpose W=8 words=1 tile={f}x186 a={f} b=700 "), res["plan"]
+        assert res["plan"].startswith(f"xpose W=8 words=1 tile={f}x{min(256, 6144 // (f | 1))} a={f} b=700 "), res["plan"]
         res = _emulate_roundtrip(fld(f, 700), 2, packed_shift=3)
         assert res["plan"].startswith(f"xpose W=8 words=1 tile={min(256, 6144 // f - 32)}x{f} a=700 b={f} outer=1 "), res["plan"]
     assert "xpose W=1 words=3 tile=7x85 " in _emulate_roundtrip(hvector(7, 1, 3, vector(900, 1, 7, contiguous(3, BYTE))), 1)["plan"]
-    # records of very few fields keep the row-by-row kernel for pack, and below four fields for unpack too
+    # records of three fields keep the row-by-row kernel for pack, of two fields for unpack too
     res = _emulate_roundtrip(rec(4, 700), 1)
-    assert "tile W" in res["plan"] and "xpose" in res["unpack_plan"]
+    assert "xpose" in res["plan"] and "xpose" in res["unpack_plan"]
     res = _emulate_roundtrip(rec(3, 700), 1)
+    assert "tile W" in res["plan"] and "xpose" in res["unpack_plan"]
+    res = _emulate_roundtrip(rec(2, 700), 1)
     assert "tile W" in res["plan"] and "tile W" in res["unpack_plan"]
     # not applicable: too few elements, elements of too many words, B stride below two elements, or switched off
     assert "tile W" in _emulate_roundtrip(transposed(20, 40, FLOAT, 4), 1)["plan"]
