@@ -78,7 +78,6 @@ hipError_t enqueue_xpose(const Launch& l, hipStream_t stream) {
     // what the kernel's lane mapping and LDS tile assume of their parameters
     const XParams& x = l.x;
     if (x.ew == 0 || x.te_a == 0 || x.te_b == 0 || x.fa_log2 > 8 || x.fb_log2 > 8 ||
-        uint64_t{x.te_a} * x.ew > (uint64_t{1} << x.fa_log2) || uint64_t{x.te_b} * x.ew > (uint64_t{1} << x.fb_log2) ||
         x.pitch < x.te_a * x.ew || uint64_t{x.te_b} * x.pitch > static_cast<uint64_t>(xpose_lds_words(l.word_log2)))
         return hipErrorInvalidValue;
     switch (l.word_log2) {

@@ -176,7 +176,8 @@ bool plan_xpose(const PlanInput& in, const std::vector<Dim>& dims, const char* t
     if (bstep < 2 * run || dims[a].count * b.count < 1024) return false;
 
     // Tile shape: square where both dimensions are long; a dimension shorter than half an edge is
-    // covered whole and the other edge grows (to 256 words per row, as far as LDS reaches).
+    // covered whole and the other edge grows (as far as LDS reaches), so that a workgroup still
+    // has tens of KiB to move.
     int64_t te_a = std::min<int64_t>(square, dims[a].count), te_b = std::min<int64_t>(square, b.count);
     // LDS row pitch in words: at least a tile row, and such that lanes walking down a tile
     // column fall into distinct banks (32 of them): any odd pitch for one-word elements, a pitch
@@ -188,9 +189,15 @@ bool plan_xpose(const PlanInput& in, const std::vector<Dim>& dims, const char* t
         return pitch;
     };
     uint32_t pitch = pitch_for(te_a);
-    if (te_a * 2 <= square) te_b = std::min({b.count, int64_t{kBlockThreads} / ew, lds_words / pitch});
+    constexpr int64_t kLongEdge = 1024;  // elements along the grown edge of a thin tile, at most
+    // a grown edge beyond one chunk of lanes is a whole number of chunks
+    auto whole_chunks = [ew](int64_t edge) {
+        const int64_t chunk = kBlockThreads / ew;
+        return edge > chunk ? edge / chunk * chunk : edge;
+    };
+    if (te_a * 2 <= square) te_b = whole_chunks(std::min({b.count, kLongEdge, lds_words / pitch}));
     else if (te_b * 2 <= square) {
-        te_a = std::min({dims[a].count, int64_t{kBlockThreads} / ew, (lds_words / te_b - 32) / ew});
+        te_a = whole_chunks(std::min({dims[a].count, kLongEdge, (lds_words / te_b - 32) / ew}));
         if (te_a < 1) return false;
         pitch = pitch_for(te_a);
     }
@@ -208,8 +215,8 @@ bool plan_xpose(const PlanInput& in, const std::vector<Dim>& dims, const char* t
     x.ew = static_cast<uint32_t>(ew);
     x.te_a = static_cast<uint32_t>(te_a);
     x.te_b = static_cast<uint32_t>(te_b);
-    x.fa_log2 = static_cast<uint32_t>(ceil_log2(static_cast<uint64_t>(te_a * ew)));
-    x.fb_log2 = static_cast<uint32_t>(ceil_log2(static_cast<uint64_t>(te_b * ew)));
+    x.fa_log2 = static_cast<uint32_t>(std::min(8, ceil_log2(static_cast<uint64_t>(te_a * ew))));
+    x.fb_log2 = static_cast<uint32_t>(std::min(8, ceil_log2(static_cast<uint64_t>(te_b * ew))));
     x.pitch = pitch;
     x.tb_stride = b.stride;
     x.tiles_a = static_cast<uint32_t>((dims[a].count + te_a - 1) / te_a);

@@ -56,7 +56,7 @@ struct XParams {
     uint32_t ca = 0, cb = 0;        // element counts of the two tiled dimensions
     uint32_t ew = 1;                // words per element (element = ew << word_log2 bytes)
     uint32_t te_a = 0, te_b = 0;    // tile edges in elements (a thin dimension is covered whole, the other grows)
-    uint32_t fa_log2 = 0, fb_log2 = 0;  // lanes along a tile row on the typed (A) and packed (B) side: >= te * ew
+    uint32_t fa_log2 = 0, fb_log2 = 0;  // lanes along a tile row on the typed (A) and packed (B) side (rows of more words are walked in chunks)
     uint32_t pitch = 0;             // LDS row pitch in words (chosen so that column accesses spread over banks)
     int64_t tb_stride = 0;          // typed bytes between B-neighbours (A-neighbours are one element apart)
     int64_t pa_stride = 0;          // packed bytes between A-neighbours (B-neighbours are one element apart)

@@ -171,36 +171,39 @@ TP_HD inline void xpose_phase(const XParams& p, uint32_t block, uint32_t tid, Me
     const uint32_t te_fast = SQUARE ? kEdge : kTypedSide ? p.te_a : p.te_b;
     const uint32_t te_slow = SQUARE ? kEdge : kTypedSide ? p.te_b : p.te_a;
     const uint32_t rows_per_pass = static_cast<uint32_t>(kBlockThreads) >> f_log2;
-    const uint32_t fast = tid & ((1u << f_log2) - 1u), slow0 = tid >> f_log2;
-    const uint32_t fe = ew == 1 ? fast : fast / ew;  // element and word within it along the fast dimension
-    const uint32_t fw = fast - fe * ew;
-    if (fe >= te_fast) return;
-    // Tile rows in groups of kGroup: all of a group's loads are issued before its first store, so
-    // that many memory accesses are in flight per thread.
-    constexpr uint32_t kGroup = 16;
-    for (uint32_t first = slow0; first < te_slow; first += kGroup * rows_per_pass) {
-        W v[kGroup];
-        bool ok[kGroup];
-        W* cell[kGroup];
-        char* far[kGroup];
+    const uint32_t lanes = 1u << f_log2, slow0 = tid >> f_log2;
+    // Tile rows longer than the lanes along them (thin tiles grown along the other dimension) are
+    // walked in chunks of `lanes` words.
+    for (uint32_t fast = tid & (lanes - 1u); fast < te_fast * ew; fast += lanes) {
+        const uint32_t fe = ew == 1 ? fast : fast / ew;  // element and word within it along the fast dimension
+        const uint32_t fw = fast - fe * ew;
+        // Tile rows in groups of kGroup: all of a group's loads are issued before its first store,
+        // so that many memory accesses are in flight per thread.
+        constexpr uint32_t kGroup = 16;
+        for (uint32_t first = slow0; first < te_slow; first += kGroup * rows_per_pass) {
+            W v[kGroup];
+            bool ok[kGroup];
+            W* cell[kGroup];
+            char* far[kGroup];
 #pragma unroll
-        for (uint32_t k = 0; k < kGroup; ++k) {
-            const uint32_t slow = first + k * rows_per_pass;
-            const uint32_t la = kTypedSide ? fe : slow, lb = kTypedSide ? slow : fe;
-            const uint32_t a = g.a0 + la, b = g.b0 + lb;
-            ok[k] = slow < te_slow && a < p.ca && b < p.cb;
-            // lanes with nothing to move address the tile's first element, which always exists
-            const uint32_t sa = ok[k] ? a : g.a0, sb = ok[k] ? b : g.b0, sw = ok[k] ? fw : 0u;
-            cell[k] = lds + (ok[k] ? lb * pitch + la * ew + fw : 0u);
-            far[k] = kTypedSide ? const_cast<char*>(xpose_typed<WLOG2>(p, g, sa, sb, sw)) : xpose_packed<WLOG2>(p, g, sa, sb, sw);
-            if (LOAD) v[k] = mem.template load<W>(far[k]);
-            else if (ok[k]) v[k] = *cell[k];
-        }
+            for (uint32_t k = 0; k < kGroup; ++k) {
+                const uint32_t slow = first + k * rows_per_pass;
+                const uint32_t la = kTypedSide ? fe : slow, lb = kTypedSide ? slow : fe;
+                const uint32_t a = g.a0 + la, b = g.b0 + lb;
+                ok[k] = slow < te_slow && a < p.ca && b < p.cb;
+                // lanes with nothing to move address the tile's first element, which always exists
+                const uint32_t sa = ok[k] ? a : g.a0, sb = ok[k] ? b : g.b0, sw = ok[k] ? fw : 0u;
+                cell[k] = lds + (ok[k] ? lb * pitch + la * ew + fw : 0u);
+                far[k] = kTypedSide ? const_cast<char*>(xpose_typed<WLOG2>(p, g, sa, sb, sw)) : xpose_packed<WLOG2>(p, g, sa, sb, sw);
+                if (LOAD) v[k] = mem.template load<W>(far[k]);
+                else if (ok[k]) v[k] = *cell[k];
+            }
 #pragma unroll
-        for (uint32_t k = 0; k < kGroup; ++k) {
-            if (!ok[k]) continue;
-            if (LOAD) *cell[k] = v[k];
-            else mem.template store<W>(far[k], v[k]);
+            for (uint32_t k = 0; k < kGroup; ++k) {
+                if (!ok[k]) continue;
+                if (LOAD) *cell[k] = v[k];
+                else mem.template store<W>(far[k], v[k]);
+            }
         }
     }
 }

@@ -83,7 +83,6 @@ void run_xpose_words(const tp::Launch& l, HostMem mem) {
     using Tile = tp::XposeTile<WLOG2>;
     const tp::XParams& x = l.x;
     if (x.ew == 0 || x.te_a == 0 || x.te_b == 0 || x.fa_log2 > 8 || x.fb_log2 > 8 ||
-        uint64_t{x.te_a} * x.ew > (uint64_t{1} << x.fa_log2) || uint64_t{x.te_b} * x.ew > (uint64_t{1} << x.fb_log2) ||
         x.pitch < x.te_a * x.ew || uint64_t{x.te_b} * x.pitch > static_cast<uint64_t>(Tile::kLdsWords)) {
         mem.c->oob++;
         return;
