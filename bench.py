@@ -58,26 +58,26 @@ def sector_bound_fraction(run: int, granule: int = 128) -> float:
 # factor a plain 64 MiB copy calibrates (FETCH_SIZE reads half the known bytes: x2; WRITE_SIZE: x1).
 # Keyed by (op, a0): (bytes fetched, bytes written).
 MEASURED_TRAFFIC = {
-    ('pack', 1): (8587607679, 68911800),
-    ('pack', 2): (4293839798, 68909561),
-    ('pack', 4): (2146952082, 70765973),
-    ('pack', 8): (1073488582, 67075217),
-    ('pack', 16): (536759071, 67090057),
-    ('pack', 32): (268393484, 67088138),
-    ('pack', 64): (134212609, 67088266),
-    ('pack', 128): (67121149, 67126263),
-    ('pack', 256): (67121149, 67123705),
+    ('pack', 1): (8586170370, 68595421),
+    ('pack', 2): (4293140520, 68408626),
+    ('pack', 4): (2146605189, 70711772),
+    ('pack', 8): (1073321530, 67078414),
+    ('pack', 16): (536674135, 67081229),
+    ('pack', 32): (268350757, 67083787),
+    ('pack', 64): (134189708, 67089417),
+    ('pack', 128): (67110271, 67111679),
+    ('pack', 256): (67109888, 67129591),
     ('pack', 512): (67108864, 67108864),
-    ('unpack', 1): (90868866, 2146406940),
-    ('unpack', 2): (76903166, 1073203470),
-    ('unpack', 4): (67301195, 536601735),
-    ('unpack', 8): (67124348, 268300868),
-    ('unpack', 16): (67123324, 134150434),
-    ('unpack', 32): (67121277, 67075217),
-    ('unpack', 64): (67121149, 67075217),
-    ('unpack', 128): (67121277, 67118459),
-    ('unpack', 256): (67121149, 67109887),
-    ('unpack', 512): (67108864, 67108736),
+    ('unpack', 1): (67107713, 2146509242),
+    ('unpack', 2): (67104130, 1073254621),
+    ('unpack', 4): (67103618, 536627311),
+    ('unpack', 8): (67102723, 268313655),
+    ('unpack', 16): (67089417, 134156828),
+    ('unpack', 32): (67102723, 67078414),
+    ('unpack', 64): (67101827, 67078414),
+    ('unpack', 128): (67101699, 67115389),
+    ('unpack', 256): (67101699, 67115261),
+    ('unpack', 512): (67108864, 67102339),
 }
 
 
@@ -137,11 +137,13 @@ def main():
 
     for _ in range(args.warmup):
         run_step()
-    plans = []
+    plans = {"pack": [], "unpack": []}
     for i, p in enumerate(points):
         h = tp.type_from_recipe(p["recipe"])
         tp.pack(arena.data_ptr() + bases[i], 1, h, packed[i], p["packed_bytes"], 0, stream)
-        plans.append(tp.last_plan().strip())
+        plans["pack"].append(tp.last_plan().strip())
+        tp.unpack(packed[i], p["packed_bytes"], 0, arena.data_ptr() + bases[i], 1, h, stream)   # the bytes just packed
+        plans["unpack"].append(tp.last_plan().strip())
 
     def new_events():
         return [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in points]
@@ -167,9 +169,10 @@ def main():
             avg_us = 1e3 * sum(ms) / len(ms)
             srt = sorted(ms)
             alg = 2 * p["packed_bytes"]
-            run = int(plans[i].split("n0=")[1].split()[0]) * int(plans[i].split("W=")[1].split()[0])
+            plan = plans[op][i]
+            run = p["a"][0] if p["a"][0] < 512 else p["packed_bytes"]
             kernels.append({
-                "op": op, "a": list(p["a"]), "plan": plans[i], "avg_us": round(avg_us, 2),
+                "op": op, "a": list(p["a"]), "plan": plan, "avg_us": round(avg_us, 2),
                 "median_us": round(1e3 * srt[len(srt) // 2], 2), "min_us": round(1e3 * srt[0], 2),
                 "algorithmic_bytes": alg, "gbs": round(alg / avg_us / 1e3, 1),
                 "frac_of_peak": round(alg / avg_us / 1e3 / HBM_PEAK_GBS, 4),
@@ -197,8 +200,9 @@ def main():
         est = rows * 256 + dominant["algorithmic_bytes"] // 2
         roofline["estimated_dram_bytes_with_line_rmw"] = est
         roofline["estimated_dram_rate_gbs"] = round(est / dominant["avg_us"] / 1e3, 1)
-        roofline["note"] = ("hardware-bound: one masked write per row, retired as a 128-byte line read-modify-write "
-                            "beyond L2 (about 22 G lines/s = HBM streaming rate); `traffic` is what the L2 counters see")
+        roofline["note"] = ("hardware-bound: one masked 32-byte write per row leaves L2 (written through at once) and is "
+                            "retired beyond it as a read-modify-write of the row's 128-byte line, which the L2-side "
+                            "counters in `traffic` do not see; about 24 G such rows per second")
     use_traffic = args.packed_bytes == PACKED_BYTES and not args.override
     if measured and use_traffic:
         roofline["traffic"] = sum(measured)

@@ -263,12 +263,15 @@ int tp_resource_stats(int kind, tp_resource_counts *out);
  *   "word"          "0" (automatic) or 1, 2, 4, 8, 16: upper limit on the access width in bytes
  *   "check_buffers" "1" (default) or "0": skip the per-call memory-residency queries (then the
  *                   buffers are taken to be GPU-addressable and large enough: the caller's duty)
- *   "nt"            "-1" (automatic) or 0..3: streaming hints, bit 0 = non-temporal loads,
- *                   bit 1 = non-temporal stores
+ *   "nt"            "-1" (automatic), 0..3 or 7: streaming hints, bit 0 = non-temporal loads,
+ *                   bit 1 = non-temporal stores, 7 = the stores also written through L2 at once
+ *   "ur"            "-1" (automatic), 1 or 4: rows per thread where a run fits one workgroup
  *   "xpose"         "1" (default) or "0": allow the transposing kernel (tiles through LDS for
  *                   blocks whose short elements are adjacent along an outer dimension)
  *   "narrow_partial_rows" "1" (default) or "0": unpack rows that are not whole aligned 64-byte
- *                   segments in 4-byte words (measured faster) rather than the widest
+ *                   segments in narrow words (measured faster) rather than the widest
+ *   "unpack_rule"   "1" (default) or "0": 0 plans such rows as before write-through stores
+ *                   (4- or 8-byte words, four rows per thread), for comparisons
  *   "max_rows_per_launch", "max_words_per_run"  1 .. 2^30: split limits (tests lower them to
  *                   exercise the multi-launch path on small inputs)
  * tp_last_plan: describes the kernel launches of the calling thread's most recent

@@ -27,6 +27,8 @@ std::atomic<int> g_max_word_log2{4};
 std::atomic<int> g_nt{-1};
 std::atomic<bool> g_check_buffers{true};
 std::atomic<bool> g_narrow_partial_rows{true};
+std::atomic<int> g_max_ur{-1};
+std::atomic<int> g_unpack_rule{1};
 std::atomic<bool> g_allow_xpose{true};
 std::atomic<int64_t> g_max_rows_per_launch{int64_t{1} << 30};
 std::atomic<int64_t> g_max_words_per_run{int64_t{1} << 30};
@@ -190,6 +192,8 @@ int plan_request(bool unpack, const TypeNode& node, const void* typed_buf, int64
     in.unpack = unpack;
     in.packed_on_host = packed_on_host;
     in.narrow_partial_rows = g_narrow_partial_rows.load(std::memory_order_relaxed);
+    in.max_ur = g_max_ur.load(std::memory_order_relaxed);
+    in.unpack_rule = g_unpack_rule.load(std::memory_order_relaxed);
     in.allow_xpose = g_allow_xpose.load(std::memory_order_relaxed);
     in.max_word_log2 = g_max_word_log2.load(std::memory_order_relaxed);
     in.nt = g_nt.load(std::memory_order_relaxed);
@@ -461,8 +465,18 @@ int tp_set_override(const char* key, const char* value) {
         return kSuccess;
     }
     if (!std::strcmp(key, "nt")) {
-        if (v < -1 || v > 3) return kErrArg;
+        if ((v < -1 || v > 3) && v != 7) return kErrArg;
         g_nt.store(static_cast<int>(v));
+        return kSuccess;
+    }
+    if (!std::strcmp(key, "ur")) {
+        if (v != -1 && v != 1 && v != 4) return kErrArg;
+        g_max_ur.store(static_cast<int>(v));
+        return kSuccess;
+    }
+    if (!std::strcmp(key, "unpack_rule")) {
+        if (v != 0 && v != 1) return kErrArg;
+        g_unpack_rule.store(static_cast<int>(v));
         return kSuccess;
     }
     if (!std::strcmp(key, "xpose")) {

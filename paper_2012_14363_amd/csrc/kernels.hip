@@ -31,7 +31,9 @@ namespace {
 
 // Memory accesses with a streaming hint.  Every byte is touched once, so loads and
 // stores can carry the non-temporal bit (`nt`): the data then does not displace
-// other lines in L2 / Infinity Cache.  NT bit 0: loads, bit 1: stores.
+// other lines in L2 / Infinity Cache.  NT bit 0: loads, bit 1: stores, bit 2: stores
+// also carry `sc1`, which has L2 write them through at once instead of holding the
+// line until something evicts it.
 // The word is accessed through a type of alignment 1: the address may be any byte, and
 // the compiler, which knows that this target takes unaligned accesses, still emits one
 // global_load/store of the full width.
@@ -46,8 +48,26 @@ struct DeviceMem {
     template <class W>
     __device__ __forceinline__ void store(char* p, const W& v) const {
         typedef W Unaligned __attribute__((aligned(1)));
-        if constexpr (NT & 2) __builtin_nontemporal_store(v, reinterpret_cast<Unaligned*>(p));
+        if constexpr (NT & 4) store_through(p, v);
+        else if constexpr (NT & 2) __builtin_nontemporal_store(v, reinterpret_cast<Unaligned*>(p));
         else *reinterpret_cast<Unaligned*>(p) = v;
+    }
+    // `global_store ... sc1 nt`.  No builtin sets both bits, hence the instruction by hand; like the
+    // plain store it takes any byte address.  After a store of more than 8 bytes the next vector
+    // instruction must not overwrite the data registers; the compiler spaces the stores it emits
+    // itself but cannot see into this one, so an s_nop follows the 16-byte form.
+    template <class W>
+    __device__ __forceinline__ static void store_through(char* p, const W& v) {
+        if constexpr (sizeof(W) == 1)
+            asm volatile("global_store_byte %0, %1, off sc1 nt" : : "v"(p), "v"(static_cast<uint32_t>(v)) : "memory");
+        else if constexpr (sizeof(W) == 2)
+            asm volatile("global_store_short %0, %1, off sc1 nt" : : "v"(p), "v"(static_cast<uint32_t>(v)) : "memory");
+        else if constexpr (sizeof(W) == 4)
+            asm volatile("global_store_dword %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
+        else if constexpr (sizeof(W) == 8)
+            asm volatile("global_store_dwordx2 %0, %1, off sc1 nt" : : "v"(p), "v"(v) : "memory");
+        else
+            asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 0" : : "v"(p), "v"(v) : "memory");
     }
 };
 
@@ -113,7 +133,9 @@ struct PickKernel {
         case 0: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 0>; break;
         case 1: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 1>; break;
         case 2: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 2>; break;
-        default: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 3>; break;
+        case 3: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 3>; break;
+        case 7: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 7>; break;
+        default: break;
         }
     }
 };

@@ -1,6 +1,7 @@
 #include "plan.hpp"
 
 #include <algorithm>
+#include <limits>
 #include <cstdio>
 
 #include "status.hpp"
@@ -8,6 +9,9 @@
 namespace tp {
 
 namespace {
+
+constexpr int64_t kPageBytes = 4096;  // rows at least this far apart each need their own address translation
+constexpr int64_t kLineBytes = 128;   // memory line: what a partial write is read-modify-written in
 
 struct Dim {
     int64_t count;
@@ -25,11 +29,12 @@ int ceil_log2(uint64_t v) {
 // Runs longer than the workgroup are cut into chunks of 256 * ux words; of ux = 1, 2, 4 the one
 // that pads the run least wins (1025 words: five chunks of 256 rather than two of 1024), the
 // larger on a tie since its row arithmetic is scalar.
-void choose_tile(uint32_t n0, Launch* l) {
+// `ur_short`: rows per thread (1 or 4) where a run fits the workgroup.
+void choose_tile(uint32_t n0, int ur_short, Launch* l) {
     if (n0 <= static_cast<uint32_t>(kBlockThreads)) {
         l->p.bx_log2 = static_cast<uint32_t>(ceil_log2(n0));
         l->ux = 1;
-        l->ur = 4;
+        l->ur = ur_short;
         return;
     }
     l->p.bx_log2 = 8;
@@ -50,6 +55,8 @@ struct Splitter {
     int word_log2;
     int64_t row_pitch;  // bytes of a full run in the packed stream
     std::vector<Launch>* out;
+    int ur_short = 4;   // rows per thread in tiles for runs that fit the workgroup
+    int nt = 3;         // streaming hints of the launches
 
     int64_t word() const { return int64_t{1} << word_log2; }
     // Words that cover a run of `bytes` (>= one word): the last one may overlap its neighbour.
@@ -76,8 +83,8 @@ struct Splitter {
             rows *= static_cast<uint64_t>(dims[d].count);
         }
         p.nrows = static_cast<uint32_t>(rows);
-        choose_tile(p.n0, &l);
-        l.nt = in.nt >= 0 ? in.nt : 3;
+        choose_tile(p.n0, ur_short, &l);
+        l.nt = nt;
         const uint32_t bx = 1u << p.bx_log2;
         const uint32_t br = kBlockThreads >> p.bx_log2;
         p.nxc = (p.n0 + bx * l.ux - 1) / (bx * l.ux);
@@ -90,7 +97,7 @@ struct Splitter {
     // Largest row count for which block ids stay below 2^30 with runs of n0 words.
     int64_t row_limit(int64_t n0) const {
         Launch probe;
-        choose_tile(static_cast<uint32_t>(n0), &probe);
+        choose_tile(static_cast<uint32_t>(n0), ur_short, &probe);
         const int64_t bx = int64_t{1} << probe.p.bx_log2;
         const int64_t br = kBlockThreads >> probe.p.bx_log2;
         const int64_t nxc = (n0 + bx * probe.ux - 1) / (bx * probe.ux);
@@ -281,31 +288,59 @@ int plan_launches(const PlanInput& in, std::vector<Launch>* out) {
     if (plan_xpose(in, dims, typed, out)) return kSuccess;
     const int64_t run = dims[0].count;
     int word_log2 = std::min({4, in.max_word_log2, 63 - __builtin_clzll(static_cast<uint64_t>(run))});
-    if (in.unpack && in.narrow_partial_rows && dims.size() > 1) {
+    int ur_short = 4, nt = 3;
+    // Do the typed rows consist of whole aligned 64-byte segments?  How far apart are rows that follow
+    // one another in the packed stream (the innermost row dimension), and how close do rows come
+    // that are written far apart in time (the outer row dimensions)?
+    bool partial_rows = false;
+    int64_t inner_pitch = 0, outer_pitch = std::numeric_limits<int64_t>::max();
+    if (dims.size() > 1) {
         uint64_t bits = static_cast<uint64_t>(run) | reinterpret_cast<uintptr_t>(typed);
-        for (size_t d = 1; d < dims.size(); ++d)
-            bits |= static_cast<uint64_t>(dims[d].stride < 0 ? -dims[d].stride : dims[d].stride);
-        if (bits & 63u) word_log2 = std::min(word_log2, run <= 1024 ? 2 : 3);
+        for (size_t d = 1; d < dims.size(); ++d) {
+            const int64_t step = dims[d].stride < 0 ? -dims[d].stride : dims[d].stride;
+            bits |= static_cast<uint64_t>(step);
+            if (dims[d].count == 1) continue;
+            if (inner_pitch == 0) inner_pitch = step;
+            else outer_pitch = std::min(outer_pitch, step);
+        }
+        partial_rows = (bits & 63u) != 0;
     }
-    // Reading mapped host memory across PCIe (zero-copy unpack): 16-byte loads were measured
-    // slower than 8- or 4-byte ones (4 MiB: 115 us against 87; 64 MiB: 1270 against 1180), writes
-    // to it do not care.
-    if (in.unpack && in.packed_on_host) word_log2 = std::min(word_log2, 3);
-    // Runs of at most 32 bytes: every run costs a whole 128-byte line whatever the word, and a
-    // wavefront whose lanes share rows touches fewer lines per instruction.  Measured: gathers run
-    // 5-13 % faster with four (or more) lanes per row than with one wide word per row, so cap the
-    // word at a quarter of the run, and at 4 bytes.
-    if (dims.size() > 1 && run <= 32) {
-        const int quarter_log2 = run >= 4 ? 63 - __builtin_clzll(static_cast<uint64_t>(run / 4)) : 0;
-        word_log2 = std::min(word_log2, std::min(2, quarter_log2));
+    if (in.unpack && !in.packed_on_host && in.unpack_rule == 1 && in.narrow_partial_rows && partial_rows &&
+        inner_pitch < kPageBytes && outer_pitch >= kLineBytes) {
+        // Rows that end in partially written memory lines, follow one another closer than a page and
+        // share no line with rows of another outer index (those L2 should keep and merge): their
+        // stores are written through L2 at once (`sc1 nt`) rather than left for eviction, a thread
+        // takes one row, not four, and a row is spread over 8 to 15 lanes.
+        nt = 7;
+        ur_short = 1;
+        const int eighth_log2 = run >= 16 ? 63 - __builtin_clzll(static_cast<uint64_t>(run / 8)) : 0;
+        word_log2 = std::min(word_log2, eighth_log2);
+    } else {
+        if (in.unpack && in.narrow_partial_rows && partial_rows) word_log2 = std::min(word_log2, run <= 1024 ? 2 : 3);
+        // Reading mapped host memory across PCIe (zero-copy unpack): 16-byte loads were measured
+        // slower than 8- or 4-byte ones (4 MiB: 115 us against 87; 64 MiB: 1270 against 1180), writes
+        // to it do not care.
+        if (in.unpack && in.packed_on_host) word_log2 = std::min(word_log2, 3);
+        // Runs of at most 32 bytes: every run costs a whole 128-byte line whatever the word, and a
+        // wavefront whose lanes share rows touches fewer lines per instruction.  Measured: gathers run
+        // 5-13 % faster with four (or more) lanes per row than with one wide word per row, so cap the
+        // word at a quarter of the run, and at 4 bytes.
+        if (dims.size() > 1 && run <= 32) {
+            const int quarter_log2 = run >= 4 ? 63 - __builtin_clzll(static_cast<uint64_t>(run / 4)) : 0;
+            word_log2 = std::min(word_log2, std::min(2, quarter_log2));
+        }
     }
-    Splitter s{in, word_log2, run, out};
+    if (in.nt >= 0) nt = in.nt;
+    if (in.max_ur == 1 || in.max_ur == 4) ur_short = in.max_ur;
+    Splitter s{in, word_log2, run, out, ur_short, nt};
     s.split_runs(dims, typed, in.packed);
     return kSuccess;
 }
 
 bool batchable(const Launch& l) {
-    return l.kind == kTile && l.p.nrd <= static_cast<uint32_t>(kBatchRowDims) && l.nblocks > 0;
+    // the batched kernel carries the three four-words-per-thread tiles and plain streaming hints
+    return l.kind == kTile && l.p.nrd <= static_cast<uint32_t>(kBatchRowDims) && l.nblocks > 0 && l.ux * l.ur == 4 &&
+           (l.nt & 4) == 0;
 }
 
 namespace {

@@ -88,7 +88,8 @@ struct Launch {
     int word_log2 = 0;  // W = 1 << word_log2 bytes per lane access
     int ux = 1;         // words per thread along the run
     int ur = 1;         // rows per thread
-    int nt = 3;         // streaming hints: bit 0 = non-temporal loads, bit 1 = non-temporal stores
+    int nt = 3;         // streaming hints: bit 0 = non-temporal loads, bit 1 = non-temporal stores,
+                        // bit 2 (with bit 1) = stores that L2 writes through at once
     uint32_t nblocks = 0;
 };
 
@@ -104,6 +105,8 @@ struct PlanInput {
     bool allow_xpose = true;          // override: permit the transposing kernel
     int max_word_log2 = 4;   // override: cap on the access width
     int nt = -1;             // override: streaming hints (-1 = planner's choice)
+    int max_ur = -1;         // override: rows per thread in tiles for runs up to 256 words (-1 = planner's choice)
+    int unpack_rule = 1;     // override: 0 = plan unpack launches as before write-through stores (for comparisons)
     int64_t max_rows_per_launch = int64_t{1} << 30;   // tests lower these to force splitting
     int64_t max_words_per_run = int64_t{1} << 30;
 };

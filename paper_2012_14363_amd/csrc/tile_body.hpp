@@ -227,6 +227,7 @@ inline bool dispatch_variant(int word_log2, int ux, int ur, uint32_t nrd, F&& f)
         if (ux == 4 && ur == 1) return by_nrd(w, I4{}, I1{});
         if (ux == 2 && ur == 2) return by_nrd(w, I2{}, I2{});
         if (ux == 1 && ur == 4) return by_nrd(w, I1{}, I4{});
+        if (ux == 1 && ur == 1) return by_nrd(w, I1{}, I1{});
         return false;
     };
     switch (word_log2) {

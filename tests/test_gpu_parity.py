@@ -160,11 +160,16 @@ def test_ragged_runs_at_any_alignment(dev, run):
     want = "tile W=16 " if run > 32 else "tile W=4 "
     for ts in (0, 1, 2, 3, 7, 13):
         for ps in (0, 1, 2, 3, 6, 15):
-            plans = roundtrip(vector(41, run, run + rng.choice((1, 3, 5, 61)), BYTE), rng.randint(1, 2), dev,
+            pitch = run + rng.choice((1, 3, 5, 61))
+            plans = roundtrip(vector(41, run, pitch, BYTE), rng.randint(1, 2), dev,
                               typed_shift=ts, packed_shift=ps, position=rng.randint(0, 3), seed=run + ts)
-            # rows that are not whole aligned 64-byte segments are written in 4-byte words, or
-            # 8-byte words beyond 1 KiB
-            narrow = "tile W=4 " if run <= 1024 else "tile W=8 "
+            # rows that are not whole aligned 64-byte segments and closer together than a page are
+            # written through, one row per thread, in words of an eighth of the row at most; rows
+            # further apart in 4-byte words, or 8-byte words beyond 1 KiB
+            if pitch < 4096:
+                narrow = f"tile W={min(16, 1 << ((run // 8).bit_length() - 1))} ux=1 ur=1 nt=7 "
+            else:
+                narrow = "tile W=4 " if run <= 1024 else "tile W=8 "
             assert plans["pack"].startswith(want) and plans["unpack"].startswith(narrow), plans
     plans = roundtrip(hvector(3, 1, 9 * (run + 7), hvector(9, 1, run + 7, contiguous(run, BYTE))), 2, dev,
                       typed_shift=3, packed_shift=1, seed=run)
@@ -261,7 +266,7 @@ def test_word_widths_forced(dev):
             say("forced word", w)
             tp.set_override("word", w)
             plans = roundtrip(t, 2, dev, seed=w)
-            assert f"W={w} " in plans["pack"] and f"W={min(w, 4)} " in plans["unpack"]
+            assert f"W={w} " in plans["pack"] and f"W={min(w, 8)} ux=1 ur=1 nt=7 " in plans["unpack"]
             # rows of whole aligned 64-byte segments: the unpack may use the wide words too
             plans = roundtrip(vector(300, 192, 256, BYTE), 2, dev, seed=w)
             assert f"W={w} " in plans["pack"] and f"W={w} " in plans["unpack"]

@@ -308,16 +308,26 @@ def test_emulated_word_width_follows_run_length_only():
             res = _emulate_roundtrip(t, 1, **kw)
             assert "tile W=16 " in res["plan"] and "n0=4 back=0 " in res["plan"]
             assert (res["unaligned"] > 0) == (shift % 16 != 0) and res["duplicates"] == 0
-    # unpack: rows made of whole aligned 64-byte segments keep 16-byte words, all others take 4
-    # (the helper puts the origin 32 bytes into a 64-byte aligned window)
-    assert "tile W=16 " in _emulate_roundtrip(t, 1, typed_shift=32)["unpack_plan"]
-    assert "tile W=16 " in _emulate_roundtrip(t, 1, typed_shift=32, position=7, packed_shift=1)["unpack_plan"]
-    assert "tile W=4 " in _emulate_roundtrip(t, 1, typed_shift=16)["unpack_plan"]
-    assert "tile W=4 " in _emulate_roundtrip(vector(16, 64, 96, BYTE), 1, typed_shift=32)["unpack_plan"]   # stride 96
+    # unpack: rows made of whole aligned 64-byte segments keep 16-byte words, four rows per thread and
+    # plain streaming stores (the helper puts the origin 32 bytes into a 64-byte aligned window)
+    assert "tile W=16 ux=1 ur=4 nt=3 " in _emulate_roundtrip(t, 1, typed_shift=32)["unpack_plan"]
+    assert "tile W=16 ux=1 ur=4 nt=3 " in _emulate_roundtrip(t, 1, typed_shift=32, position=7, packed_shift=1)["unpack_plan"]
+    # all other rows, if closer together than a page: written through, one row per thread, 8 to 15 lanes per row
+    assert "tile W=8 ux=1 ur=1 nt=7 bx=8 n0=8 " in _emulate_roundtrip(t, 1, typed_shift=16)["unpack_plan"]
+    assert "tile W=8 ux=1 ur=1 nt=7 " in _emulate_roundtrip(vector(16, 64, 96, BYTE), 1, typed_shift=32)["unpack_plan"]   # stride 96
     res = _emulate_roundtrip(vector(16, 200, 512, BYTE), 1)
-    assert "W=16 " in res["plan"] and "W=4 " in res["unpack_plan"] and "n0=50 back=0" in res["unpack_plan"]
+    assert "W=16 " in res["plan"] and "W=16 ux=1 ur=1 nt=7 bx=16 n0=13 back=8" in res["unpack_plan"]
     res = _emulate_roundtrip(vector(16, 201, 512, BYTE), 1, typed_shift=3)
-    assert "W=16 " in res["plan"] and "W=4 " in res["unpack_plan"] and "n0=51 back=3" in res["unpack_plan"]
+    assert "W=16 " in res["plan"] and "W=16 ux=1 ur=1 nt=7 bx=16 n0=13 back=7" in res["unpack_plan"]
+    wt = lambda n, **kw: _emulate_roundtrip(vector(16, n, 128, BYTE), 1, **kw)["unpack_plan"]  # noqa: E731
+    assert "W=8 ux=1 ur=1 nt=7 bx=16 n0=13 back=4 " in wt(100) and "W=4 ux=1 ur=1 nt=7 bx=8 n0=8 " in wt(32)
+    assert "W=2 ux=1 ur=1 nt=7 bx=16 n0=12 " in wt(24) and "W=2 ux=1 ur=1 nt=7 bx=8 n0=8 " in wt(16)
+    assert "W=1 ux=1 ur=1 nt=7 bx=16 n0=12 " in wt(12) and "W=1 ux=1 ur=1 nt=7 bx=8 n0=8 " in wt(8)
+    assert "W=1 ux=1 ur=1 nt=7 bx=4 n0=3 " in wt(3, typed_shift=5) and "W=1 ux=1 ur=1 nt=7 bx=1 n0=1 " in wt(1)
+    # rows a page or more apart keep the narrow words, four rows per thread and plain streaming stores
+    assert "W=4 ux=1 ur=4 nt=3 bx=64 n0=50 " in _emulate_roundtrip(vector(16, 200, 4096, BYTE), 1)["unpack_plan"]
+    assert "W=8 ux=1 ur=4 nt=3 " in _emulate_roundtrip(vector(5, 1040, 8192, BYTE), 1)["unpack_plan"]
+    assert "W=16 ux=1 ur=1 nt=7 bx=256 n0=129 back=8 " in _emulate_roundtrip(vector(5, 2056, 2100, BYTE), 1)["unpack_plan"]
     assert "W=16 " in _emulate_roundtrip(contiguous(4099, BYTE), 1, typed_shift=1)["unpack_plan"]  # one run: no rows
     assert "W=4 " in _emulate_roundtrip(t, 1, max_word=4)["plan"]
     assert "W=16 bx=4 n0=3 back=0 " in _emulate_roundtrip(vector(16, 48, 64, BYTE), 1)["plan"].replace("ux=1 ur=4 nt=3 ", "")
@@ -436,7 +446,11 @@ def test_emulated_transposing_tiles():
     assert "tile W" in _emulate_roundtrip(transposed(64, 64, contiguous(31, BYTE), 31), 1)["plan"]     # 31 words of 1
     assert "tile W" in _emulate_roundtrip(transposed(64, 64, contiguous(80, BYTE), 80), 1)["plan"]
     assert "tile W" in _emulate_roundtrip(hvector(64, 1, 8, hvector(64, 1, 12, contiguous(8, BYTE))), 1)["plan"]   # overlapping rows
-    assert "tile W" in _emulate_roundtrip(transposed(64, 64, FLOAT, 4), 1, allow_xpose=False)["plan"]
+    res = _emulate_roundtrip(transposed(64, 64, FLOAT, 4), 1, allow_xpose=False)
+    assert "tile W" in res["plan"]
+    # rows of different outer index share memory lines here: L2 is left to merge them (no write-through)
+    assert "tile W=1 ux=1 ur=4 nt=3 " in res["unpack_plan"], res["unpack_plan"]
+    assert "ur=4 nt=3 " in _emulate_roundtrip(rec(2, 700), 1)["unpack_plan"]
     assert "tile W" in _emulate_roundtrip(transposed(64, 64, FLOAT, 4), 1, max_rows_per_launch=1000)["plan"]
 
 
