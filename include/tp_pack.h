@@ -268,8 +268,8 @@ int tp_resource_stats(int kind, tp_resource_counts *out);
  *   "ur"            "-1" (automatic), 1 or 4: rows per thread where a run fits one workgroup
  *   "xpose"         "1" (default) or "0": allow the transposing kernel (tiles through LDS for
  *                   blocks whose short elements are adjacent along an outer dimension)
- *   "narrow_partial_rows" "1" (default) or "0": unpack rows that are not whole aligned 64-byte
- *                   segments in narrow words (measured faster) rather than the widest
+ *   "narrow_partial_rows" "1" (default) or "0": unpack rows that are not whole aligned 128-byte
+ *                   memory lines in narrow words (measured faster) rather than the widest
  *   "unpack_rule"   "1" (default) or "0": 0 plans such rows as before write-through stores
  *                   (4- or 8-byte words, four rows per thread), for comparisons
  *   "max_rows_per_launch", "max_words_per_run"  1 .. 2^30: split limits (tests lower them to

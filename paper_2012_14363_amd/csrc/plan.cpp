@@ -277,19 +277,20 @@ int plan_launches(const PlanInput& in, std::vector<Launch>* out) {
     // Reading the typed side (pack): 16 bytes wherever a run holds that much - equal to narrower
     // words on runs they divide, up to 20 % faster on the others, and 2-4 times faster than the
     // bytes that natural alignment would force at odd addresses or run lengths.
-    // Writing the typed side (unpack): a row that is not made of whole aligned 64-byte segments
-    // ends in partially written memory lines, which the memory system read-modify-writes, and how
-    // the row's stores are split over instructions then matters.  Measured on 60 MiB of rows at
-    // 128- to 8192-byte pitch (4 / 8 / 16-byte words, us): 100-byte rows 34 / 44 / 49, 200: 33 / 40 /
-    // 40, 1000: 29 / 33 / 35, but 1040: 34 / 27 / 27, 2056: 30 / 27 / 32, 4100: 27 / 26 / 25.  So such
-    // rows take 4-byte words up to 1 KiB and 8-byte words beyond; rows of whole aligned
-    // segments keep 16.
+    // Writing the typed side (unpack): a row that is not made of whole aligned 128-byte lines ends
+    // in partially written lines, which the memory system read-modify-writes, and how the row's
+    // stores are issued then matters: see the write-through rule below.  Where that rule does not
+    // apply, the earlier one holds.  It was measured with plain streaming stores and four rows per
+    // thread on 60 MiB of rows at 128- to 8192-byte pitch (4 / 8 / 16-byte words, us): 100-byte rows
+    // 34 / 44 / 49, 200: 33 / 40 / 40, 1000: 29 / 33 / 35, but 1040: 34 / 27 / 27, 2056: 30 / 27 / 32,
+    // 4100: 27 / 26 / 25: 4-byte words up to 1 KiB and 8-byte words beyond.  Rows of whole aligned
+    // lines keep 16.
     const char* typed = in.typed + sb.start;
     if (plan_xpose(in, dims, typed, out)) return kSuccess;
     const int64_t run = dims[0].count;
     int word_log2 = std::min({4, in.max_word_log2, 63 - __builtin_clzll(static_cast<uint64_t>(run))});
     int ur_short = 4, nt = 3;
-    // Do the typed rows consist of whole aligned 64-byte segments?  How far apart are rows that follow
+    // Do the typed rows consist of whole aligned 128-byte memory lines?  How far apart are rows that follow
     // one another in the packed stream (the innermost row dimension), and how close do rows come
     // that are written far apart in time (the outer row dimensions)?
     bool partial_rows = false;
@@ -303,7 +304,7 @@ int plan_launches(const PlanInput& in, std::vector<Launch>* out) {
             if (inner_pitch == 0) inner_pitch = step;
             else outer_pitch = std::min(outer_pitch, step);
         }
-        partial_rows = (bits & 63u) != 0;
+        partial_rows = (bits & static_cast<uint64_t>(kLineBytes - 1)) != 0;
     }
     if (in.unpack && !in.packed_on_host && in.unpack_rule == 1 && in.narrow_partial_rows && partial_rows &&
         inner_pitch < kPageBytes && outer_pitch >= kLineBytes) {

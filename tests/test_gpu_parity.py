@@ -163,7 +163,7 @@ def test_ragged_runs_at_any_alignment(dev, run):
             pitch = run + rng.choice((1, 3, 5, 61))
             plans = roundtrip(vector(41, run, pitch, BYTE), rng.randint(1, 2), dev,
                               typed_shift=ts, packed_shift=ps, position=rng.randint(0, 3), seed=run + ts)
-            # rows that are not whole aligned 64-byte segments and closer together than a page are
+            # rows that are not whole aligned 128-byte lines and closer together than a page are
             # written through, one row per thread, in words of an eighth of the row at most; rows
             # further apart in 4-byte words, or 8-byte words beyond 1 KiB
             if pitch < 4096:
@@ -267,7 +267,7 @@ def test_word_widths_forced(dev):
             tp.set_override("word", w)
             plans = roundtrip(t, 2, dev, seed=w)
             assert f"W={w} " in plans["pack"] and f"W={min(w, 8)} ux=1 ur=1 nt=7 " in plans["unpack"]
-            # rows of whole aligned 64-byte segments: the unpack may use the wide words too
+            # rows of whole 64-byte segments: the unpack may use the wide words too
             plans = roundtrip(vector(300, 192, 256, BYTE), 2, dev, seed=w)
             assert f"W={w} " in plans["pack"] and f"W={w} " in plans["unpack"]
     finally:

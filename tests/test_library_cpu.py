@@ -248,8 +248,8 @@ def _emulate_roundtrip(t, incount, *, typed_shift=0, packed_shift=0, position=0,
     origin = -lo + pad + typed_shift
     n = hi - lo + 2 * pad + typed_shift
     rng = np.random.default_rng(hash((str(t), incount)) & 0xFFFFFFFF)
-    typed_store = np.zeros(n + 64, dtype=np.uint8)
-    base = (-typed_store.ctypes.data) % 64          # 64-byte aligned window, then shifted
+    typed_store = np.zeros(n + 128, dtype=np.uint8)
+    base = (-typed_store.ctypes.data) % 128         # 128-byte aligned window, then shifted
     typed = typed_store[base:base + n]
     typed[:] = rng.integers(0, 256, n, dtype=np.uint8)
     packed_store = np.zeros(size + position + 64 + 16, dtype=np.uint8)
@@ -308,10 +308,13 @@ def test_emulated_word_width_follows_run_length_only():
             res = _emulate_roundtrip(t, 1, **kw)
             assert "tile W=16 " in res["plan"] and "n0=4 back=0 " in res["plan"]
             assert (res["unaligned"] > 0) == (shift % 16 != 0) and res["duplicates"] == 0
-    # unpack: rows made of whole aligned 64-byte segments keep 16-byte words, four rows per thread and
-    # plain streaming stores (the helper puts the origin 32 bytes into a 64-byte aligned window)
-    assert "tile W=16 ux=1 ur=4 nt=3 " in _emulate_roundtrip(t, 1, typed_shift=32)["unpack_plan"]
-    assert "tile W=16 ux=1 ur=4 nt=3 " in _emulate_roundtrip(t, 1, typed_shift=32, position=7, packed_shift=1)["unpack_plan"]
+    # unpack: rows made of whole aligned 128-byte lines keep 16-byte words, four rows per thread and
+    # plain streaming stores (the helper puts the origin 32 bytes into a 128-byte aligned window)
+    full = vector(16, 128, 256, BYTE)
+    assert "tile W=16 ux=1 ur=4 nt=3 " in _emulate_roundtrip(full, 1, typed_shift=96)["unpack_plan"]
+    assert "tile W=16 ux=1 ur=4 nt=3 " in _emulate_roundtrip(full, 1, typed_shift=96, position=7, packed_shift=1)["unpack_plan"]
+    assert "tile W=16 ux=1 ur=1 nt=7 " in _emulate_roundtrip(full, 1, typed_shift=32)["unpack_plan"]       # rows start mid-line
+    assert "tile W=8 ux=1 ur=1 nt=7 " in _emulate_roundtrip(t, 1, typed_shift=96)["unpack_plan"]             # half lines
     # all other rows, if closer together than a page: written through, one row per thread, 8 to 15 lanes per row
     assert "tile W=8 ux=1 ur=1 nt=7 bx=8 n0=8 " in _emulate_roundtrip(t, 1, typed_shift=16)["unpack_plan"]
     assert "tile W=8 ux=1 ur=1 nt=7 " in _emulate_roundtrip(vector(16, 64, 96, BYTE), 1, typed_shift=32)["unpack_plan"]   # stride 96
