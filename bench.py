@@ -58,26 +58,26 @@ def sector_bound_fraction(run: int, granule: int = 128) -> float:
 # factor a plain 64 MiB copy calibrates (FETCH_SIZE reads half the known bytes: x2; WRITE_SIZE: x1).
 # Keyed by (op, a0): (bytes fetched, bytes written).
 MEASURED_TRAFFIC = {
-    ('pack', 1): (8586170370, 68595421),
-    ('pack', 2): (4293140520, 68408626),
-    ('pack', 4): (2146605189, 70711772),
-    ('pack', 8): (1073321530, 67078414),
-    ('pack', 16): (536674135, 67081229),
-    ('pack', 32): (268350757, 67083787),
-    ('pack', 64): (134189708, 67089417),
-    ('pack', 128): (67110271, 67111679),
-    ('pack', 256): (67109888, 67129591),
+    ('pack', 1): (8586169602, 68900290),
+    ('pack', 2): (4293139113, 68956194),
+    ('pack', 4): (2146593162, 70752354),
+    ('pack', 8): (1073316540, 67070614),
+    ('pack', 16): (536673751, 67079952),
+    ('pack', 32): (268350246, 67085453),
+    ('pack', 64): (134189708, 67084302),
+    ('pack', 128): (67110015, 67116412),
+    ('pack', 256): (67109888, 67120122),
     ('pack', 512): (67108864, 67108864),
-    ('unpack', 1): (67107713, 2146509242),
-    ('unpack', 2): (67104130, 1073254621),
-    ('unpack', 4): (67103618, 536627311),
-    ('unpack', 8): (67102723, 268313655),
-    ('unpack', 16): (67089417, 134156828),
-    ('unpack', 32): (67102723, 67078414),
-    ('unpack', 64): (67101827, 67078414),
-    ('unpack', 128): (67101699, 67115389),
-    ('unpack', 256): (67101699, 67115261),
-    ('unpack', 512): (67108864, 67102339),
+    ('unpack', 1): (67104514, 2146259642),
+    ('unpack', 2): (67104130, 1073129821),
+    ('unpack', 4): (67102851, 536564911),
+    ('unpack', 8): (67102723, 268282455),
+    ('unpack', 16): (67089417, 134141228),
+    ('unpack', 32): (67102723, 67070614),
+    ('unpack', 64): (67102723, 67070614),
+    ('unpack', 128): (67101699, 67115644),
+    ('unpack', 256): (67101699, 67100421),
+    ('unpack', 512): (67108864, 67095943),
 }
 
 
