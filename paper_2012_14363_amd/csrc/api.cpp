@@ -162,7 +162,7 @@ int data_span(const TypeNode& node, int64_t count, int64_t* lo, int64_t* hi) {
 // Checks the buffers of a request that has passed check_request and appends its planned launches
 // to `launches`.  `packed` is the contiguous buffer as the caller passed it.
 int plan_request(bool unpack, const TypeNode& node, const void* typed_buf, int64_t count, const void* packed,
-                 int64_t position, BufferMap* memory, std::vector<Launch>* launches) {
+                 int64_t position, BufferMap* memory, std::vector<Launch>* launches, bool batched = false) {
     // Query the first selected byte, not the origin: MPI lets the origin lie outside the
     // allocation (negative strides, lower bounds above zero); the data never does.
     const char* typed = static_cast<const char*>(typed_buf);
@@ -191,6 +191,7 @@ int plan_request(bool unpack, const TypeNode& node, const void* typed_buf, int64
     in.packed = const_cast<char*>(packed_view);
     in.unpack = unpack;
     in.packed_on_host = packed_on_host;
+    in.batched = batched;
     in.narrow_partial_rows = g_narrow_partial_rows.load(std::memory_order_relaxed);
     in.max_ur = g_max_ur.load(std::memory_order_relaxed);
     in.unpack_rule = g_unpack_rule.load(std::memory_order_relaxed);
@@ -273,7 +274,7 @@ int transfer_batch(bool unpack, int n, const void* const* typed_bufs, const int*
     for (int i = 0; i < n; ++i) {
         if (sizes[i] == 0) continue;
         const int rc =
-            plan_request(unpack, *nodes[i], typed_bufs[i], counts[i], packed_buf, offsets[i], &memory, &launches);
+            plan_request(unpack, *nodes[i], typed_bufs[i], counts[i], packed_buf, offsets[i], &memory, &launches, true);
         if (rc != kSuccess) return rc;
     }
     std::vector<BatchParams> batches;

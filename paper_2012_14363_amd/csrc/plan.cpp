@@ -12,6 +12,7 @@ namespace {
 
 constexpr int64_t kPageBytes = 4096;  // rows at least this far apart each need their own address translation
 constexpr int64_t kLineBytes = 128;   // memory line: what a partial write is read-modify-written in
+constexpr int64_t kSoloRows = int64_t{1} << 20, kSoloBytes = int64_t{8} << 20;  // batch requests worth their own launch
 
 struct Dim {
     int64_t count;
@@ -306,8 +307,13 @@ int plan_launches(const PlanInput& in, std::vector<Launch>* out) {
         }
         partial_rows = (bits & static_cast<uint64_t>(kLineBytes - 1)) != 0;
     }
+    // A request of a batch call keeps a plan the batched kernel can run unless it is large enough
+    // for a launch of its own to pay (a launch costs about 5 us on the stream).
+    int64_t rows = 1;
+    for (size_t d = 1; d < dims.size(); ++d) rows *= dims[d].count;
+    const bool own_launch = !in.batched || rows >= kSoloRows || rows * run >= kSoloBytes;
     if (in.unpack && !in.packed_on_host && in.unpack_rule == 1 && in.narrow_partial_rows && partial_rows &&
-        inner_pitch < kPageBytes && outer_pitch >= kLineBytes) {
+        inner_pitch < kPageBytes && outer_pitch >= kLineBytes && own_launch) {
         // Rows that end in partially written memory lines, follow one another closer than a page and
         // share no line with rows of another outer index (those L2 should keep and merge): their
         // stores are written through L2 at once (`sc1 nt`) rather than left for eviction, a thread

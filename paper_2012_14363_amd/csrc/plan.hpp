@@ -101,6 +101,7 @@ struct PlanInput {
     char* packed = nullptr;        // contiguous buffer + position
     bool unpack = false;     // direction: the typed side is written
     bool packed_on_host = false;   // the contiguous buffer is mapped host memory (zero-copy)
+    bool batched = false;          // one request of a batch call: small ones should stay fit for a batched launch
     bool narrow_partial_rows = true;  // override: unpack rows with partial memory lines in narrow words
     bool allow_xpose = true;          // override: permit the transposing kernel
     int max_word_log2 = 4;   // override: cap on the access width

@@ -233,6 +233,7 @@ int emul_transfer_batch(int unpack, int n, const int* ndims, const int64_t* star
         in.typed = typed_buf + origins[i];
         in.packed = packed_buf + pos;
         in.unpack = unpack != 0;
+        in.batched = true;
         std::vector<tp::Launch> mine;
         const int rc = tp::plan_launches(in, &mine);
         if (rc != tp::kSuccess) return rc;
