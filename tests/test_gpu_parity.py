@@ -648,6 +648,33 @@ def test_batch_mixed_types_and_fallback(dev):
     assert (packed.cpu().numpy() == 0x11).all()
 
 
+def test_batch_unpack_large_requests_take_their_own_launch(dev):
+    # small requests ride in the batched launch; requests of 2^20 rows or 8 MiB that write through get
+    # a launch of their own (one row per thread, sc1 nt stores); the bytes are the oracle's either way
+    reqs, typed_len = [], 0
+    for t in (vector(300, 24, 64, BYTE), vector((1 << 20) + 5, 3, 16, BYTE), vector(100, 200, 512, BYTE),
+              vector(45000, 200, 512, BYTE), hvector(7, 1, 5000, vector(40, 10, 100, BYTE))):
+        d, n = cc.blocks(t, 1)
+        origin = typed_len + 1
+        typed_len = origin + int((d + n).max()) + 16
+        reqs.append((t, 1, origin))
+    handles = [tp.type_from_recipe(t) for t, _, _ in reqs]
+    total = sum(tp.type_size(h) for h in handles)
+    packed_h = W.random_bytes(11, total + 3)
+    packed = to_dev(packed_h, dev)
+    back = torch.full((typed_len,), 0xA5, dtype=torch.uint8, device=dev)
+    say("batch unpack, small and large requests", total, "bytes")
+    bb = tp.Batch([back.data_ptr() + o for _, _, o in reqs], [1] * len(reqs), handles)
+    assert tp.unpack_batch(packed, total + 3, 3, bb) == total + 3
+    plan = tp.last_plan()
+    assert plan.count("batch") == 1 and plan.count("ur=1 nt=7") == 2 and "rows=1048581" in plan and "rows=45000" in plan, plan
+    want = np.full(typed_len, 0xA5, np.uint8)
+    pos = 3
+    for t, c, o in reqs:
+        pos = cc.unpack(packed_h, pos, want, o, c, t)
+    assert np.array_equal(back.cpu().numpy(), want)
+
+
 def test_batch_many_objects_of_one_type(dev):
     # 300 separately addressed objects of the nested 4-level type: 8 batched launches instead of 300
     c = W.configs.cfg5()
