@@ -328,8 +328,9 @@ def extras(W, tp, torch, np, dev, stream):
     us = timed(unaligned, n=12)
     tp.set_override("word", 0)
     res["copy_64MiB_odd_addresses_bytewise"] = {"us": round(us, 2), "gbs": round(2 * odd / us / 1e3, 1)}
-    # rows at odd addresses (typed + 1, packed + 3): 200-byte and 67-byte runs at 512-byte pitch
-    for run in (200, 67):
+    # rows at odd addresses (typed + 1, packed + 3): 200-, 67- and 24-byte runs at 512-byte pitch; the unpack
+    # also as it was planned before stores were written through (override unpack_rule = 0)
+    for run in (200, 67, 24):
         rows_o = (48 << 20) // run
         t_o = tp.type_from_recipe(W.vector(rows_o, run, 512, W.BYTE))
         typed_o = [torch.empty(rows_o * 512 + 64, dtype=torch.uint8, device=dev).fill_(i + 1) for i in range(2)]
@@ -345,6 +346,11 @@ def extras(W, tp, torch, np, dev, stream):
                 tp.unpack_async(dsts[j].data_ptr() + poff, rows_o * run, 0, typed_o[j % 2].data_ptr() + toff, 1, t_o, stream)
                 k[0] += 1
             entry[label] = {"pack_us": round(timed(pk, n=12), 1), "unpack_us": round(timed(un, n=12), 1)}
+            tp.set_override("unpack_rule", 0)
+            try:
+                entry[label]["unpack_us_nt_stores_four_rows_per_thread"] = round(timed(un, n=12), 1)
+            finally:
+                tp.set_override("unpack_rule", 1)
         res[f"rows_of_{run}B_at_512B_pitch_48MiB"] = entry
         del typed_o
     del srcs, dsts
