@@ -263,8 +263,8 @@ int tp_resource_stats(int kind, tp_resource_counts *out);
  *   "word"          "0" (automatic) or 1, 2, 4, 8, 16: upper limit on the access width in bytes
  *   "check_buffers" "1" (default) or "0": skip the per-call memory-residency queries (then the
  *                   buffers are taken to be GPU-addressable and large enough: the caller's duty)
- *   "nt"            "-1" (automatic), 0..3 or 7: streaming hints, bit 0 = non-temporal loads,
- *                   bit 1 = non-temporal stores, 7 = the stores also written through L2 at once
+ *   "nt"            "-1" (automatic), 0..3, 6 (unpack only) or 7: streaming hints, bit 0 = non-temporal
+ *                   loads, bit 1 = non-temporal stores, bit 2 = the stores also written through L2 at once
  *   "ur"            "-1" (automatic), 1 or 4: rows per thread where a run fits one workgroup
  *   "xpose"         "1" (default) or "0": allow the transposing kernel (tiles through LDS for
  *                   blocks whose short elements are adjacent along an outer dimension)
@@ -272,6 +272,10 @@ int tp_resource_stats(int kind, tp_resource_counts *out);
  *                   memory lines in narrow words (measured faster) rather than the widest
  *   "unpack_rule"   "1" (default) or "0": 0 plans such rows as before write-through stores
  *                   (4- or 8-byte words, four rows per thread), for comparisons
+ *   "stage"         "-1" (automatic: from 2^20 rows), "0" (never) or "1" (wherever it applies): staged
+ *                   unpack of rows of one word at 512-, 256- or 128-byte pitch (a read-only pass per chunk
+ *                   of packed bytes, then the stores); "stage_bytes" 4096 .. 2^30: packed bytes per chunk
+ *                   (default 16 MiB); "stage_grid" "0" (automatic) or the workgroups of such a launch
  *   "max_rows_per_launch", "max_words_per_run"  1 .. 2^30: split limits (tests lower them to
  *                   exercise the multi-launch path on small inputs)
  * tp_last_plan: describes the kernel launches of the calling thread's most recent

@@ -52,6 +52,11 @@ struct DeviceMem {
         else if constexpr (NT & 2) __builtin_nontemporal_store(v, reinterpret_cast<Unaligned*>(p));
         else *reinterpret_cast<Unaligned*>(p) = v;
     }
+    // Keeps a loaded value alive without using it (prefetch passes).
+    template <class W>
+    __device__ __forceinline__ void consume(const W& v) const {
+        asm volatile("" : : "v"(v));
+    }
     // `global_store ... sc1 nt`.  No builtin sets both bits, hence the instruction by hand; like the
     // plain store it takes any byte address.  After a store of more than 8 bytes the next vector
     // instruction must not overwrite the data registers; the compiler spaces the stores it emits
@@ -73,7 +78,15 @@ struct DeviceMem {
 
 template <int WLOG2, int UX, int UR, bool UNPACK, int NRD, int NT>
 __global__ void __launch_bounds__(kBlockThreads) tile_kernel(const KParams p) {
-    tile_thread<WLOG2, UX, UR, UNPACK, NRD>(p, blockIdx.x, threadIdx.x, DeviceMem<NT>{});
+    // one workgroup per tile, or (staged unpack) fewer workgroups that each take every gridDim.x-th tile
+    for (uint32_t tile = blockIdx.x; tile < p.ntiles; tile += gridDim.x)
+        tile_thread<WLOG2, UX, UR, UNPACK, NRD>(p, tile, threadIdx.x, DeviceMem<NT>{});
+}
+
+// Read-only pass of a staged unpack: plain (cached) loads, so the bytes stay in this XCD's L2.
+__global__ void __launch_bounds__(kBlockThreads) prefetch_kernel(const PrefetchParams f) {
+    for (uint32_t tile = blockIdx.x; tile < f.ntiles; tile += gridDim.x)
+        prefetch_thread(f, tile, threadIdx.x, DeviceMem<0>{});
 }
 
 // Transposing tiles through LDS (tile_body.hpp: xpose_phase).
@@ -134,6 +147,9 @@ struct PickKernel {
         case 1: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 1>; break;
         case 2: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 2>; break;
         case 3: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 3>; break;
+        case 6:
+            if constexpr (UNPACK) fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 6>;
+            break;
         case 7: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 7>; break;
         default: break;
         }
@@ -143,9 +159,20 @@ struct PickKernel {
 }  // namespace
 
 hipError_t enqueue(const Launch& l, bool unpack, hipStream_t stream) {
+    if (l.nblocks == 0 || l.grid > l.nblocks) return hipErrorInvalidValue;
+    const dim3 grid(l.grid ? l.grid : l.nblocks), block(kBlockThreads);
     if (l.kind == kXpose) {
-        if (l.nblocks == 0) return hipErrorInvalidValue;
+        if (l.grid) return hipErrorInvalidValue;
         return unpack ? enqueue_xpose<true>(l, stream) : enqueue_xpose<false>(l, stream);
+    }
+    if (l.kind == kPrefetch) {
+        // what prefetch_thread assumes of its parameters
+        const PrefetchParams& f = l.f;
+        if (!f.base || f.bytes < 16 || f.tile_bytes == 0 || f.tile_bytes % 16 || f.ntiles != l.nblocks ||
+            (f.bytes + f.tile_bytes - 1) / f.tile_bytes != f.ntiles)
+            return hipErrorInvalidValue;
+        hipLaunchKernelGGL(prefetch_kernel, grid, block, 0, stream, f);
+        return hipGetLastError();
     }
     const KParams p = kernel_params(l);
     KernelFn fn = nullptr;
@@ -158,8 +185,8 @@ hipError_t enqueue(const Launch& l, bool unpack, hipStream_t stream) {
         pick.nt = l.nt;
         if (dispatch_launch(l, p.nrd, pick)) fn = pick.fn;
     }
-    if (!fn || l.nblocks == 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(fn, dim3(l.nblocks), dim3(kBlockThreads), 0, stream, p);
+    if (!fn) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(fn, grid, block, 0, stream, p);
     return hipGetLastError();
 }
 

@@ -13,6 +13,7 @@ namespace {
 constexpr int64_t kPageBytes = 4096;  // rows at least this far apart each need their own address translation
 constexpr int64_t kLineBytes = 128;   // memory line: what a partial write is read-modify-written in
 constexpr int64_t kSoloRows = int64_t{1} << 20, kSoloBytes = int64_t{8} << 20;  // batch requests worth their own launch
+constexpr int64_t kStagedRows = int64_t{1} << 20;  // fewer rows do not repay the extra passes of a staged unpack
 
 struct Dim {
     int64_t count;
@@ -58,6 +59,7 @@ struct Splitter {
     std::vector<Launch>* out;
     int ur_short = 4;   // rows per thread in tiles for runs that fit the workgroup
     int nt = 3;         // streaming hints of the launches
+    uint32_t grid = 0;  // workgroups per launch (0 = one per tile)
 
     int64_t word() const { return int64_t{1} << word_log2; }
     // Words that cover a run of `bytes` (>= one word): the last one may overlap its neighbour.
@@ -92,6 +94,7 @@ struct Splitter {
         p.xc_div = make_fastdiv(p.nxc);
         const uint64_t nrc = (rows + uint64_t{br} * l.ur - 1) / (uint64_t{br} * l.ur);
         l.nblocks = static_cast<uint32_t>(nrc * p.nxc);
+        if (grid) l.grid = std::min(grid, l.nblocks);
         out->push_back(l);
     }
 
@@ -254,6 +257,56 @@ bool plan_xpose(const PlanInput& in, const std::vector<Dim>& dims, const char* t
     return true;
 }
 
+// Staged unpack of tiny rows.  Partially written memory lines retire about 1.5 times faster when
+// (a) the lines written at one time are exactly 512 bytes apart and (b) no read from HBM falls
+// between the writes (measured; plan_launches has the figures).  For rows of one word each at a
+// pitch of 512 bytes, or of 256 or 128 taken in 2 or 4 passes over every 2nd or 4th row, the
+// launch is therefore cut into chunks of `stage_bytes` packed bytes, and every chunk becomes a
+// read-only pass that brings its packed bytes into L2 followed by the store passes, all with the
+// same few workgroups taking the same tiles: workgroup ids map to XCDs round-robin, so a tile's
+// bytes wait in the L2 its stores will ask.  Returns false where this does not apply.
+bool plan_staged(const PlanInput& in, const std::vector<Dim>& dims, const char* typed, std::vector<Launch>* out) {
+    if (dims.size() != 2) return false;
+    const int64_t run = dims[0].count, rows = dims[1].count, pitch = dims[1].stride;
+    const int64_t step = pitch < 0 ? -pitch : pitch;
+    if (run > 16 || (run & (run - 1)) != 0 || (int64_t{1} << in.max_word_log2) < run) return false;
+    if (step != 128 && step != 256 && step != 512) return false;
+    if (in.stage != 1 && rows < kStagedRows) return false;
+    if (in.max_rows_per_launch != (int64_t{1} << 30) || in.max_words_per_run != (int64_t{1} << 30)) return false;
+    const int64_t passes = 512 / step;
+    // the passes give up the locality of neighbouring rows, which costs more the more of each line the
+    // rows fill: measured to pay for 1- to 16-byte rows at 512-byte pitch, up to 4 bytes at 256, 1 byte at 128
+    if (run * passes * passes > 16) return false;
+    const int64_t tile_rows = int64_t{kBlockThreads} * passes;  // rows of all passes that share one tile index
+    if (tile_rows * run % 16 != 0) return false;
+    int64_t chunk_rows = std::max<int64_t>(in.stage_bytes / run, 1) / tile_rows * tile_rows;
+    if (chunk_rows == 0) chunk_rows = tile_rows;
+    const uint32_t grid = in.stage_grid > 0 ? static_cast<uint32_t>(in.stage_grid) : (run == 1 ? 256u : 512u);
+    int word_log2 = 0;
+    while ((int64_t{1} << word_log2) < run) ++word_log2;
+    for (int64_t lo = 0; lo < rows; lo += chunk_rows) {
+        const int64_t n = std::min(chunk_rows, rows - lo);
+        if (n * run >= 16) {
+            Launch l;
+            l.kind = kPrefetch;
+            l.f.base = in.packed + lo * run;
+            l.f.bytes = static_cast<uint64_t>(n * run);
+            l.f.tile_bytes = static_cast<uint32_t>(tile_rows * run);
+            l.f.ntiles = static_cast<uint32_t>((n + tile_rows - 1) / tile_rows);
+            l.nblocks = l.f.ntiles;
+            l.grid = std::min(grid, l.nblocks);
+            out->push_back(l);
+        }
+        for (int64_t p = 0; p < passes && p < n; ++p) {
+            // rows lo + p, lo + p + passes, ...: `passes` rows apart on both sides
+            Splitter s{in, word_log2, run * passes, out, 1, in.nt >= 0 ? in.nt : 6, grid};
+            const std::vector<Dim> sub = {{run, 1}, {(n - p + passes - 1) / passes, pitch * passes}};
+            s.add(sub, typed + (lo + p) * pitch, in.packed + (lo + p) * run);
+        }
+    }
+    return true;
+}
+
 }  // namespace
 
 int plan_launches(const PlanInput& in, std::vector<Launch>* out) {
@@ -314,6 +367,7 @@ int plan_launches(const PlanInput& in, std::vector<Launch>* out) {
     const bool own_launch = !in.batched || rows >= kSoloRows || rows * run >= kSoloBytes;
     if (in.unpack && !in.packed_on_host && in.unpack_rule == 1 && in.narrow_partial_rows && partial_rows &&
         inner_pitch < kPageBytes && outer_pitch >= kLineBytes && own_launch) {
+        if (in.stage != 0 && !in.batched && plan_staged(in, dims, typed, out)) return kSuccess;
         // Rows that end in partially written memory lines, follow one another closer than a page and
         // share no line with rows of another outer index (those L2 should keep and merge): their
         // stores are written through L2 at once (`sc1 nt`) rather than left for eviction, a thread
@@ -347,7 +401,7 @@ int plan_launches(const PlanInput& in, std::vector<Launch>* out) {
 bool batchable(const Launch& l) {
     // the batched kernel carries the three four-words-per-thread tiles and plain streaming hints
     return l.kind == kTile && l.p.nrd <= static_cast<uint32_t>(kBatchRowDims) && l.nblocks > 0 && l.ux * l.ur == 4 &&
-           (l.nt & 4) == 0;
+           (l.nt & 4) == 0 && l.grid == 0;
 }
 
 namespace {
@@ -435,9 +489,20 @@ std::string describe(const std::vector<Launch>& launches) {
             text += line;
             continue;
         }
-        std::snprintf(line, sizeof line, "tile W=%d ux=%d ur=%d nt=%d bx=%u n0=%u back=%u rows=%u nrd=%u blocks=%u\n",
+        if (l.kind == kPrefetch) {
+            std::snprintf(line, sizeof line, "prefetch bytes=%llu tile=%u blocks=%u grid=%u\n",
+                          static_cast<unsigned long long>(l.f.bytes), l.f.tile_bytes, l.nblocks, l.grid ? l.grid : l.nblocks);
+            text += line;
+            continue;
+        }
+        std::snprintf(line, sizeof line, "tile W=%d ux=%d ur=%d nt=%d bx=%u n0=%u back=%u rows=%u nrd=%u blocks=%u",
                       1 << l.word_log2, l.ux, l.ur, l.nt, 1u << l.p.bx_log2, l.p.n0, l.p.tail_back, l.p.nrows, l.p.nrd, l.nblocks);
         text += line;
+        if (l.grid) {
+            std::snprintf(line, sizeof line, " grid=%u", l.grid);
+            text += line;
+        }
+        text += "\n";
     }
     return text;
 }

@@ -36,6 +36,7 @@ struct KParams {
     uint32_t nxc = 1;               // x-chunks per row; block id = row_chunk * nxc + x_chunk
     uint32_t nrd = 0;               // row dimensions in use
     uint32_t tail_back = 0;         // n0 * W - run bytes (0 .. W-1): how far the last word is pulled back
+    uint32_t ntiles = 0;            // tiles of the launch; workgroup g takes tiles g, g + gridDim.x, ...
     FastDiv xc_div;
     FastDiv rdiv[kMaxDims];
     uint32_t rcount[kMaxDims] = {};
@@ -79,18 +80,30 @@ inline bool xpose_is_square(const XParams& x, int word_log2) {
 }
 constexpr int xpose_lds_words(int word_log2) { return xpose_fast_words(word_log2) * (xpose_fast_words(word_log2) + 32); }
 
-enum LaunchKind : int { kTile = 0, kXpose = 1 };
+// A pass that only reads (staged unpack, plan.cpp): the workgroup of tile t loads bytes
+// [t * tile_bytes, (t + 1) * tile_bytes) of `base`, cut off at `bytes`, so that they sit in the L2 of
+// the XCD that the same tile of the store passes behind it runs on.
+struct PrefetchParams {
+    const char* base = nullptr;
+    uint64_t bytes = 0;       // at least 16
+    uint32_t tile_bytes = 0;  // a multiple of 16
+    uint32_t ntiles = 0;
+};
+
+enum LaunchKind : int { kTile = 0, kXpose = 1, kPrefetch = 2 };
 
 struct Launch {
     KParams p;
     XParams x;          // kind == kXpose only
+    PrefetchParams f;   // kind == kPrefetch only
     int kind = kTile;
     int word_log2 = 0;  // W = 1 << word_log2 bytes per lane access
     int ux = 1;         // words per thread along the run
     int ur = 1;         // rows per thread
     int nt = 3;         // streaming hints: bit 0 = non-temporal loads, bit 1 = non-temporal stores,
                         // bit 2 (with bit 1) = stores that L2 writes through at once
-    uint32_t nblocks = 0;
+    uint32_t nblocks = 0;  // tiles
+    uint32_t grid = 0;     // workgroups launched; 0 = one per tile
 };
 
 struct PlanInput {
@@ -108,6 +121,9 @@ struct PlanInput {
     int nt = -1;             // override: streaming hints (-1 = planner's choice)
     int max_ur = -1;         // override: rows per thread in tiles for runs up to 256 words (-1 = planner's choice)
     int unpack_rule = 1;     // override: 0 = plan unpack launches as before write-through stores (for comparisons)
+    int stage = -1;          // override: staged unpack of tiny rows: -1 = planner's choice, 0 = never, 1 = wherever it applies
+    int64_t stage_bytes = int64_t{16} << 20;  // override: packed bytes per staged chunk
+    int stage_grid = 0;      // override: workgroups of a staged launch (0 = planner's choice)
     int64_t max_rows_per_launch = int64_t{1} << 30;   // tests lower these to force splitting
     int64_t max_words_per_run = int64_t{1} << 30;
 };

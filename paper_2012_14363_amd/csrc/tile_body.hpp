@@ -105,6 +105,18 @@ TP_HD inline void tile_thread(const P& p, uint32_t block, uint32_t tid, Mem mem)
             if (ok[ur][ux]) mem.template store<W>(dst[ur][ux], v[ur][ux]);
 }
 
+// Thread `tid` of the workgroup that prefetches tile `tile`: 16-byte loads over the tile's bytes, the
+// values dropped.  The last word ends with the bytes (they are at least 16).
+template <class Mem>
+TP_HD inline void prefetch_thread(const PrefetchParams& f, uint32_t tile, uint32_t tid, Mem mem) {
+    const uint64_t lo = static_cast<uint64_t>(tile) * f.tile_bytes;
+    const uint64_t hi = lo + f.tile_bytes < f.bytes ? lo + f.tile_bytes : f.bytes;
+    for (uint64_t off = lo + static_cast<uint64_t>(tid) * 16; off < hi; off += static_cast<uint64_t>(kBlockThreads) * 16) {
+        const uint64_t at = off + 16 <= f.bytes ? off : f.bytes - 16;
+        mem.consume(mem.template load<Word16>(f.base + at));
+    }
+}
+
 // ------------------------------------------------------------------ transposing tiles
 template <int WLOG2>
 struct XposeTile {
@@ -335,6 +347,7 @@ inline bool dispatch_launch(const Launch& l, uint32_t nrd, F&& f) {
 // unrolled, division-free variant serves it.
 inline KParams kernel_params(const Launch& l) {
     KParams p = l.p;
+    p.ntiles = l.nblocks;
     if (p.nrd == 0) {
         p.nrd = 1;
         p.rcount[0] = 1;

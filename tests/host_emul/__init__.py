@@ -32,7 +32,7 @@ def _load():
         L = ctypes.CDLL(_LIB)
         i64, p64, vp = ctypes.c_int64, ctypes.POINTER(ctypes.c_int64), ctypes.c_void_p
         L.emul_transfer.argtypes = [ctypes.c_int, ctypes.c_int, i64, p64, p64, i64, i64, vp, i64, i64, vp, i64, i64,
-                                    ctypes.c_int, i64, i64, ctypes.c_int, vp, p64, ctypes.c_char_p, i64]
+                                    ctypes.c_int, i64, i64, ctypes.c_int, ctypes.c_int, i64, vp, p64, ctypes.c_char_p, i64]
         L.emul_transfer.restype = ctypes.c_int
         pint = ctypes.POINTER(ctypes.c_int)
         L.emul_transfer_batch.argtypes = [ctypes.c_int, ctypes.c_int, pint, p64, p64, p64, p64, p64, p64, p64, vp, i64,
@@ -142,7 +142,8 @@ def fastdiv_mismatches(small_limit, random_pairs, seed):
 
 
 def transfer(unpack, block, extent, count, typed, origin, packed, position, *, max_word=16,
-             max_rows_per_launch=1 << 30, max_words_per_run=1 << 30, allow_xpose=True, count_writes=True):
+             max_rows_per_launch=1 << 30, max_words_per_run=1 << 30, allow_xpose=True, stage=-1, stage_bytes=0,
+             count_writes=True):
     """Emulates tp_pack / tp_unpack on host numpy uint8 arrays.
 
     `block` = (start, counts, strides) as returned by tp_type_get_strided_block.
@@ -152,14 +153,15 @@ def transfer(unpack, block, extent, count, typed, origin, packed, position, *, m
     arr = ctypes.c_int64 * nd
     dst = typed if unpack else packed
     wc = np.zeros(dst.size, dtype=np.uint8) if count_writes else None
-    result = (ctypes.c_int64 * 5)()
+    result = (ctypes.c_int64 * 6)()
     text = ctypes.create_string_buffer(1 << 16)
     rc = _load().emul_transfer(int(unpack), nd, start, arr(*counts), arr(*strides), extent, count,
                                typed.ctypes.data, typed.size, origin, packed.ctypes.data, packed.size, position,
                                {1: 0, 2: 1, 4: 2, 8: 3, 16: 4}[max_word], max_rows_per_launch, max_words_per_run,
-                               int(allow_xpose), wc.ctypes.data if wc is not None else None, result, text, len(text))
+                               int(allow_xpose), stage, stage_bytes, wc.ctypes.data if wc is not None else None, result,
+                               text, len(text))
     return {"rc": rc, "oob": result[0], "unaligned": result[1], "rewritten": result[2], "launches": result[3],
-            "duplicates": result[4], "plan": text.value.decode(), "write_count": wc}
+            "duplicates": result[4], "prefetched_span": result[5], "plan": text.value.decode(), "write_count": wc}
 
 
 def transfer_batch(unpack, requests, typed, packed, position, count_writes=True):

@@ -30,6 +30,8 @@ struct Checks {
     int64_t unaligned = 0;  // accesses at an address that is no multiple of their width (legal)
     int64_t rewritten = 0;  // destination bytes written again with a different value
     int64_t duplicates = 0; // destination bytes written again with the same value
+    const char* prefetched_lo = nullptr;  // what the read-only passes of a staged unpack cover
+    const char* prefetched_hi = nullptr;
 };
 
 struct HostMem {
@@ -58,6 +60,8 @@ struct HostMem {
         }
         std::memcpy(p, &v, sizeof(W));
     }
+    template <class W>
+    void consume(const W&) const {}
 };
 
 // Visitor for dispatch_launch: run every workgroup and thread of the variant a launch names.
@@ -116,7 +120,21 @@ bool run_xpose(const tp::Launch& l, bool unpack, HostMem mem) {
 
 // Runs one planned launch of either kind; false if it names no kernel variant.
 bool run_launch(const tp::Launch& l, bool unpack, Checks* c) {
+    if (l.grid > l.nblocks) return false;
     if (l.kind == tp::kXpose) return run_xpose(l, unpack, HostMem{c});
+    if (l.kind == tp::kPrefetch) {
+        // the launcher's checks, then every tile (whichever workgroup takes it) and thread
+        const tp::PrefetchParams& f = l.f;
+        if (!unpack || !f.base || f.bytes < 16 || f.tile_bytes == 0 || f.tile_bytes % 16 || f.ntiles != l.nblocks ||
+            (f.bytes + f.tile_bytes - 1) / f.tile_bytes != f.ntiles)
+            return false;
+        c->prefetched_lo = c->prefetched_lo ? std::min(c->prefetched_lo, f.base) : f.base;
+        c->prefetched_hi = std::max(c->prefetched_hi, f.base + f.bytes);
+        for (uint32_t b = 0; b < l.nblocks; ++b)
+            for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t)
+                tp::prefetch_thread(f, b, t, HostMem{c});
+        return true;
+    }
     const tp::KParams p = tp::kernel_params(l);
     if (unpack) {
         RunLaunch<true> run{&p, l.nblocks, HostMem{c}};
@@ -142,8 +160,8 @@ extern "C" {
 int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, const int64_t* strides, int64_t extent,
                   int64_t count, char* typed_buf, int64_t typed_len, int64_t origin, char* packed_buf,
                   int64_t packed_len, int64_t position, int max_word_log2, int64_t max_rows_per_launch,
-                  int64_t max_words_per_run, int allow_xpose, uint8_t* write_count, int64_t* result,
-                  char* plan_text, int64_t plan_text_len) {
+                  int64_t max_words_per_run, int allow_xpose, int stage, int64_t stage_bytes, uint8_t* write_count,
+                  int64_t* result, char* plan_text, int64_t plan_text_len) {
     tp::PlanInput in;
     in.block.ndims = ndims;
     in.block.start = start;
@@ -160,6 +178,8 @@ int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, c
     in.max_rows_per_launch = max_rows_per_launch;
     in.max_words_per_run = max_words_per_run;
     in.allow_xpose = allow_xpose != 0;
+    in.stage = stage;
+    if (stage_bytes > 0) in.stage_bytes = stage_bytes;
     std::vector<tp::Launch> launches;
     const int rc = tp::plan_launches(in, &launches);
     if (rc != tp::kSuccess) return rc;
@@ -176,6 +196,7 @@ int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, c
     result[2] = c.rewritten;
     result[3] = static_cast<int64_t>(launches.size());
     result[4] = c.duplicates;
+    result[5] = c.prefetched_hi - c.prefetched_lo;   // span of the packed bytes the read-only passes cover
     return 0;
 }
 

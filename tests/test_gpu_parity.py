@@ -182,6 +182,34 @@ def test_ragged_runs_at_any_alignment(dev, run):
         tp.set_override("word", 0)
 
 
+def test_staged_unpack_of_tiny_rows(dev):
+    # a million rows or more of one word each at 512-, 256- or 128-byte pitch: per 16 MiB of packed bytes a
+    # read-only pass and store passes over rows 512 bytes apart; exact bytes, gaps untouched, any addresses
+    for run, pitch, rows, ts, ps, pos in ((1, 512, (1 << 20) + 77, 0, 0, 0), (2, 512, (1 << 20) + 3, 1, 3, 5),
+                                          (16, 512, (1 << 21) + 1, 8, 0, 0), (4, 256, (5 << 20) + 333, 2, 1, 1),
+                                          (1, 128, (17 << 20) + 9, 0, 5, 2)):
+        say("staged unpack, run", run, "pitch", pitch, "rows", rows)
+        plans = roundtrip(vector(rows, run, pitch, BYTE), 1, dev, typed_shift=ts, packed_shift=ps, position=pos, seed=rows)
+        passes = 512 // pitch
+        chunks = -(-rows * run // (16 << 20))
+        assert plans["unpack"].count("prefetch") == chunks, plans["unpack"]
+        assert plans["unpack"].count(f"tile W={run} ux=1 ur=1 nt=6 ") == chunks * passes, plans["unpack"]
+        assert "prefetch" not in plans["pack"]
+    try:   # forced on a short message, with small chunks and few workgroups; and switched off
+        tp.set_override("stage", 1)
+        tp.set_override("stage_bytes", 8192)
+        tp.set_override("stage_grid", 8)
+        plans = roundtrip(vector(70001, 2, 256, BYTE), 1, dev, typed_shift=1, seed=5)
+        assert plans["unpack"].count("prefetch") == 18 and " grid=8" in plans["unpack"], plans["unpack"][:300]
+        tp.set_override("stage", 0)
+        plans = roundtrip(vector((1 << 20) + 77, 1, 512, BYTE), 1, dev, seed=6)
+        assert "prefetch" not in plans["unpack"] and "nt=7" in plans["unpack"]
+    finally:
+        tp.set_override("stage", -1)
+        tp.set_override("stage_bytes", 16 << 20)
+        tp.set_override("stage_grid", 0)
+
+
 def test_transposing_tiles(dev):
     # short elements adjacent along an outer dimension (a matrix walked column by column): tiles
     # through LDS, both directions, ragged edges, every word width, elements of several words,

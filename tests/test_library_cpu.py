@@ -271,8 +271,8 @@ def _emulate_roundtrip(t, incount, *, typed_shift=0, packed_shift=0, position=0,
     assert res["duplicates"] <= 15 * max(runs, 1), (t, res)
 
     if not py.has_overlap(t, incount):
-        dst_store = np.zeros(n + 64, dtype=np.uint8)
-        dbase = (-dst_store.ctypes.data) % 64      # aligned like the buffer that was packed from
+        dst_store = np.zeros(n + 128, dtype=np.uint8)
+        dbase = (-dst_store.ctypes.data) % 128     # aligned like the buffer that was packed from
         dst = dst_store[dbase:dbase + n]
         dst[:] = 0xA5
         back = host_emul.transfer(True, block, ex, incount, dst, origin, packed, position, **kw)
@@ -281,6 +281,7 @@ def _emulate_roundtrip(t, incount, *, typed_shift=0, packed_shift=0, position=0,
         cc.unpack(packed, position, want, origin, incount, t)
         assert np.array_equal(dst, want), (t, back["plan"])
         res["unpack_plan"] = back["plan"]
+        res["unpack_prefetched_span"] = back["prefetched_span"]
     if h >= 12:
         tp.type_free(h)
     return res
@@ -290,7 +291,8 @@ def test_emulated_kernels_match_oracle_on_random_types():
     rng = random.Random(303)
     for i, t in enumerate(_random_types(301, 250, allow_negative=True, allow_zero=False)):
         _emulate_roundtrip(t, rng.randint(1, 3), typed_shift=rng.choice((0, 0, 1, 2, 4, 8)),
-                           packed_shift=rng.choice((0, 0, 1, 2, 4, 8)), position=rng.choice((0, 3, 16)))
+                           packed_shift=rng.choice((0, 0, 1, 2, 4, 8)), position=rng.choice((0, 3, 16)),
+                           stage=rng.choice((-1, 1)), stage_bytes=rng.choice((0, 4096)))
 
 
 @pytest.mark.parametrize("a0", [1, 2, 4, 8, 16, 48, 64, 200, 512, 1040, 4100, 4112])
@@ -351,6 +353,47 @@ def test_emulated_word_width_follows_run_length_only():
     assert "W=4 bx=8 n0=6 back=0 " in short(24, typed_shift=1, packed_shift=3)      # whatever the addresses
     assert "W=4 bx=8 n0=7 back=3 " in short(25) and "W=1 bx=4 n0=3 " in short(3)
     assert "W=16 bx=4 n0=3 back=15 " in short(33)
+
+
+def test_emulated_staged_unpack_of_tiny_rows():
+    # rows of one word at a pitch of 512, 256 or 128 bytes: chunks of packed bytes, each a read-only pass
+    # followed by store passes whose rows are 512 bytes apart, all with the same few workgroups
+    res = _emulate_roundtrip(vector(5000, 1, 512, BYTE), 1, stage=1, stage_bytes=4096)
+    lines = res["unpack_plan"].splitlines()
+    assert lines[0] == "prefetch bytes=4096 tile=256 blocks=16 grid=16", lines
+    assert lines[1] == "tile W=1 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=4096 nrd=1 blocks=16 grid=16", lines
+    assert lines[2] == "prefetch bytes=904 tile=256 blocks=4 grid=4" and " rows=904 " in lines[3] and len(lines) == 4, lines
+    assert res["unpack_prefetched_span"] == 5000 and "prefetch" not in res["plan"]
+    # four passes over every fourth row at 128-byte pitch; the packed rows of a pass are four words apart
+    res = _emulate_roundtrip(vector(12001, 1, 128, BYTE), 1, stage=1, stage_bytes=8192, typed_shift=3, position=5)
+    lines = res["unpack_plan"].splitlines()
+    assert lines[0] == "prefetch bytes=8192 tile=1024 blocks=8 grid=8", lines
+    assert [ln.split(" bx")[0] for ln in lines[1:5]] == ["tile W=1 ux=1 ur=1 nt=6"] * 4 and all(" rows=2048 " in ln for ln in lines[1:5])
+    assert lines[5] == "prefetch bytes=3809 tile=1024 blocks=4 grid=4", lines
+    assert [int(ln.split("rows=")[1].split()[0]) for ln in lines[6:]] == [953, 952, 952, 952], lines
+    assert res["unpack_prefetched_span"] == 12001
+    # two passes at 256-byte pitch, 4-byte rows, odd addresses on both sides (a chunk is one tile of both passes at least)
+    res = _emulate_roundtrip(vector(2700, 4, 256, BYTE), 1, stage=1, stage_bytes=4096, typed_shift=1, packed_shift=3, position=2)
+    assert res["unpack_plan"].count("prefetch") == 3 and res["unpack_plan"].count("tile W=4 ux=1 ur=1 nt=6") == 6
+    res = _emulate_roundtrip(hvector(300, 1, -512, contiguous(2, BYTE)), 1, stage=1, stage_bytes=4096)     # negative pitch
+    assert "prefetch" in res["unpack_plan"] and "tile W=2 ux=1 ur=1 nt=6" in res["unpack_plan"]
+    # a last chunk of fewer than 16 bytes goes without its read-only pass; fewer rows than passes
+    res = _emulate_roundtrip(vector(4101, 1, 512, BYTE), 1, stage=1, stage_bytes=4096)
+    assert res["unpack_plan"].count("prefetch") == 1 and res["unpack_plan"].count("tile W=1") == 2
+    res = _emulate_roundtrip(vector(3, 1, 128, BYTE), 1, stage=1)
+    assert "prefetch" not in res["unpack_plan"] and res["unpack_plan"].count("tile W=1") == 3     # 3 bytes: no read-only pass
+    res = _emulate_roundtrip(vector(19, 1, 128, BYTE), 1, stage=1)
+    assert res["unpack_plan"].count("prefetch") == 1 and res["unpack_plan"].count("tile W=1") == 4
+    # where it does not apply: rows of several words, other pitches, more row dimensions, too few rows unless forced
+    for t in (vector(3000, 3, 512, BYTE), vector(3000, 4, 384, BYTE), vector(3000, 32, 512, BYTE), vector(3000, 4, 1024, BYTE),
+              vector(3000, 8, 256, BYTE), vector(3000, 2, 128, BYTE), hvector(3, 1, 1 << 20, vector(1000, 4, 512, BYTE))):
+        assert "prefetch" not in _emulate_roundtrip(t, 1, stage=1)["unpack_plan"], t
+    assert "prefetch" not in _emulate_roundtrip(vector(5000, 1, 512, BYTE), 1)["unpack_plan"]
+    assert "prefetch" not in _emulate_roundtrip(vector(5000, 1, 512, BYTE), 1, stage=0)["unpack_plan"]
+    # objects that abut fold into rows and are staged together; objects apart are an outer dimension
+    res = _emulate_roundtrip(subarray((512, 512), (512, 4), (0, 0), "C", BYTE), 3, stage=1)
+    assert "prefetch bytes=6144 " in res["unpack_plan"] and " rows=1536 " in res["unpack_plan"]
+    assert "prefetch" not in _emulate_roundtrip(vector(512, 4, 512, BYTE), 3, stage=1)["unpack_plan"]
 
 
 def test_emulated_ragged_runs_at_any_alignment():
