@@ -68,28 +68,29 @@ def sector_bound_fraction(run: int, granule: int = 128) -> float:
 # HBM bytes per launch of the sweep's kernels at 64 MiB packed, from rocprofv3 --pmc FETCH_SIZE and
 # WRITE_SIZE runs of this script (profiles/tile_kernel_strided_block_sweep_64MiB_hbm_traffic.md): counter KiB x 1024 x the
 # factor a plain 64 MiB copy calibrates (FETCH_SIZE reads half the known bytes: x2; WRITE_SIZE: x1).
-# Keyed by (op, a0): (bytes fetched, bytes written).
+# Keyed by (op, a0): (bytes fetched, bytes written), per call (a staged unpack is 8 launches; its store passes
+# fetch the packed bytes a second time under the profiler, which starts every dispatch with a cold L2).
 MEASURED_TRAFFIC = {
-    ('pack', 1): (8586169602, 68900290),
-    ('pack', 2): (4293139113, 68956194),
-    ('pack', 4): (2146593162, 70752354),
-    ('pack', 8): (1073316540, 67070614),
-    ('pack', 16): (536673751, 67079952),
-    ('pack', 32): (268350246, 67085453),
-    ('pack', 64): (134189708, 67084302),
-    ('pack', 128): (67110015, 67116412),
-    ('pack', 256): (67109888, 67120122),
+    ('pack', 1): (8585954523, 72397743),
+    ('pack', 2): (4293047948, 72013875),
+    ('pack', 4): (2146545596, 70380851),
+    ('pack', 8): (1073285464, 66985443),
+    ('pack', 16): (536667616, 67017896),
+    ('pack', 32): (268346282, 67020579),
+    ('pack', 64): (134189325, 67094682),
+    ('pack', 128): (67110015, 67056097),
+    ('pack', 256): (67109888, 67090977),
     ('pack', 512): (67108864, 67108864),
-    ('unpack', 1): (67104514, 2146259642),
-    ('unpack', 2): (67104130, 1073129821),
-    ('unpack', 4): (67102851, 536564911),
-    ('unpack', 8): (67102723, 268282455),
-    ('unpack', 16): (67089417, 134141228),
-    ('unpack', 32): (67102723, 67070614),
-    ('unpack', 64): (67102723, 67070614),
-    ('unpack', 128): (67101699, 67115644),
-    ('unpack', 256): (67101699, 67100421),
-    ('unpack', 512): (67108864, 67095943),
+    ('unpack', 1): (134428572, 2143534189),
+    ('unpack', 2): (134428572, 1071767094),
+    ('unpack', 4): (134428572, 535883547),
+    ('unpack', 8): (134387632, 267941774),
+    ('unpack', 16): (134428572, 133970887),
+    ('unpack', 32): (67100676, 66985443),
+    ('unpack', 64): (67102723, 66985443),
+    ('unpack', 128): (67109888, 67091488),
+    ('unpack', 256): (67110015, 67071173),
+    ('unpack', 512): (67108864, 67039105),
 }
 
 
@@ -211,8 +212,8 @@ def main():
                             "brings the packed bytes into L2, then the store pass); `avg_launch_us`, `achieved` and "
                             "`traffic` are per call, all launches included.  Hardware-bound: every row leaves L2 as one "
                             "masked 32-byte write and is read-modify-written beyond L2, where the L2-side counters in "
-                            "`traffic` do not see it; such rows retire at about 24 G/s in general and at about 30 G/s in "
-                            "this staged form")
+                            "`traffic` do not see it; such rows retire at about 24 G/s in general and at about 37 G/s in "
+                            "this staged form (rows 512 bytes apart, no read from HBM between the writes)")
     use_traffic = args.packed_bytes == PACKED_BYTES and not args.override
     if measured and use_traffic:
         roofline["traffic"] = sum(measured)

@@ -85,8 +85,7 @@ __global__ void __launch_bounds__(kBlockThreads) tile_kernel(const KParams p) {
 
 // Read-only pass of a staged unpack: plain (cached) loads, so the bytes stay in this XCD's L2.
 __global__ void __launch_bounds__(kBlockThreads) prefetch_kernel(const PrefetchParams f) {
-    for (uint32_t tile = blockIdx.x; tile < f.ntiles; tile += gridDim.x)
-        prefetch_thread(f, tile, threadIdx.x, DeviceMem<0>{});
+    prefetch_thread(f, blockIdx.x, gridDim.x, threadIdx.x, DeviceMem<0>{});
 }
 
 // Transposing tiles through LDS (tile_body.hpp: xpose_phase).
@@ -168,7 +167,7 @@ hipError_t enqueue(const Launch& l, bool unpack, hipStream_t stream) {
     if (l.kind == kPrefetch) {
         // what prefetch_thread assumes of its parameters
         const PrefetchParams& f = l.f;
-        if (!f.base || f.bytes < 16 || f.tile_bytes == 0 || f.tile_bytes % 16 || f.ntiles != l.nblocks ||
+        if (!f.base || f.bytes < 16 || f.tile_bytes < 16 || (f.tile_bytes & (f.tile_bytes - 1)) || f.ntiles != l.nblocks ||
             (f.bytes + f.tile_bytes - 1) / f.tile_bytes != f.ntiles)
             return hipErrorInvalidValue;
         hipLaunchKernelGGL(prefetch_kernel, grid, block, 0, stream, f);

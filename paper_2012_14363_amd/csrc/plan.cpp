@@ -14,6 +14,7 @@ constexpr int64_t kPageBytes = 4096;  // rows at least this far apart each need 
 constexpr int64_t kLineBytes = 128;   // memory line: what a partial write is read-modify-written in
 constexpr int64_t kSoloRows = int64_t{1} << 20, kSoloBytes = int64_t{8} << 20;  // batch requests worth their own launch
 constexpr int64_t kStagedRows = int64_t{1} << 20;  // fewer rows do not repay the extra passes of a staged unpack
+constexpr uint32_t kStagedGrid = 256;              // workgroups of a staged launch: one per compute unit
 
 struct Dim {
     int64_t count;
@@ -278,10 +279,10 @@ bool plan_staged(const PlanInput& in, const std::vector<Dim>& dims, const char* 
     // rows fill: measured to pay for 1- to 16-byte rows at 512-byte pitch, up to 4 bytes at 256, 1 byte at 128
     if (run * passes * passes > 16) return false;
     const int64_t tile_rows = int64_t{kBlockThreads} * passes;  // rows of all passes that share one tile index
-    if (tile_rows * run % 16 != 0) return false;
+    // tile_rows * run bytes per tile: a power of two, at least 256
     int64_t chunk_rows = std::max<int64_t>(in.stage_bytes / run, 1) / tile_rows * tile_rows;
     if (chunk_rows == 0) chunk_rows = tile_rows;
-    const uint32_t grid = in.stage_grid > 0 ? static_cast<uint32_t>(in.stage_grid) : (run == 1 ? 256u : 512u);
+    const uint32_t grid = in.stage_grid > 0 ? static_cast<uint32_t>(in.stage_grid) : kStagedGrid;
     int word_log2 = 0;
     while ((int64_t{1} << word_log2) < run) ++word_log2;
     for (int64_t lo = 0; lo < rows; lo += chunk_rows) {

@@ -86,7 +86,7 @@ constexpr int xpose_lds_words(int word_log2) { return xpose_fast_words(word_log2
 struct PrefetchParams {
     const char* base = nullptr;
     uint64_t bytes = 0;       // at least 16
-    uint32_t tile_bytes = 0;  // a multiple of 16
+    uint32_t tile_bytes = 0;  // a power of two, at least 16
     uint32_t ntiles = 0;
 };
 

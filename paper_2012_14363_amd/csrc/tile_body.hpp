@@ -105,15 +105,33 @@ TP_HD inline void tile_thread(const P& p, uint32_t block, uint32_t tid, Mem mem)
             if (ok[ur][ux]) mem.template store<W>(dst[ur][ux], v[ur][ux]);
 }
 
-// Thread `tid` of the workgroup that prefetches tile `tile`: 16-byte loads over the tile's bytes, the
-// values dropped.  The last word ends with the bytes (they are at least 16).
+// Thread `tid` of workgroup `block` of `nblocks` in a read-only pass.  The workgroup owns tiles
+// block, block + nblocks, ...; its threads walk the 16-byte words of all of them as one list, four
+// loads in flight per thread, and drop the values.  The last word ends with the bytes (they are
+// at least 16).  tile_bytes is a power of two (>= 16), so the list index splits with a shift.
 template <class Mem>
-TP_HD inline void prefetch_thread(const PrefetchParams& f, uint32_t tile, uint32_t tid, Mem mem) {
-    const uint64_t lo = static_cast<uint64_t>(tile) * f.tile_bytes;
-    const uint64_t hi = lo + f.tile_bytes < f.bytes ? lo + f.tile_bytes : f.bytes;
-    for (uint64_t off = lo + static_cast<uint64_t>(tid) * 16; off < hi; off += static_cast<uint64_t>(kBlockThreads) * 16) {
-        const uint64_t at = off + 16 <= f.bytes ? off : f.bytes - 16;
-        mem.consume(mem.template load<Word16>(f.base + at));
+TP_HD inline void prefetch_thread(const PrefetchParams& f, uint32_t block, uint32_t nblocks, uint32_t tid, Mem mem) {
+    if (block >= f.ntiles) return;
+    uint32_t wlog = 0;
+    while ((16u << wlog) < f.tile_bytes) ++wlog;                  // words per tile = 1 << wlog
+    const uint64_t my_tiles = (static_cast<uint64_t>(f.ntiles) - block + nblocks - 1) / nblocks;
+    const uint64_t words = my_tiles << wlog;
+    constexpr int kInFlight = 4;
+    for (uint64_t first = tid; first < words; first += static_cast<uint64_t>(kBlockThreads) * kInFlight) {
+        Word16 v[kInFlight];
+        bool ok[kInFlight];
+#pragma unroll
+        for (int k = 0; k < kInFlight; ++k) {
+            const uint64_t idx = first + static_cast<uint64_t>(k) * kBlockThreads;
+            const uint64_t tile = block + (idx >> wlog) * nblocks;
+            const uint64_t off = tile * f.tile_bytes + ((idx & ((uint64_t{1} << wlog) - 1)) << 4);
+            ok[k] = idx < words && off < f.bytes;
+            const uint64_t at = off + 16 <= f.bytes ? off : f.bytes - 16;
+            if (ok[k]) v[k] = mem.template load<Word16>(f.base + at);
+        }
+#pragma unroll
+        for (int k = 0; k < kInFlight; ++k)
+            if (ok[k]) mem.consume(v[k]);
     }
 }
 

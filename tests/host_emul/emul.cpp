@@ -30,6 +30,7 @@ struct Checks {
     int64_t unaligned = 0;  // accesses at an address that is no multiple of their width (legal)
     int64_t rewritten = 0;  // destination bytes written again with a different value
     int64_t duplicates = 0; // destination bytes written again with the same value
+    int64_t loads = 0;      // all loads
     const char* prefetched_lo = nullptr;  // what the read-only passes of a staged unpack cover
     const char* prefetched_hi = nullptr;
 };
@@ -42,6 +43,7 @@ struct HostMem {
     template <class W>
     W load(const char* p) const {
         W v{};
+        c->loads++;
         if (!inside(p, sizeof(W))) { c->oob++; return v; }
         if (reinterpret_cast<uintptr_t>(p) % sizeof(W)) c->unaligned++;
         std::memcpy(&v, p, sizeof(W));
@@ -125,14 +127,18 @@ bool run_launch(const tp::Launch& l, bool unpack, Checks* c) {
     if (l.kind == tp::kPrefetch) {
         // the launcher's checks, then every tile (whichever workgroup takes it) and thread
         const tp::PrefetchParams& f = l.f;
-        if (!unpack || !f.base || f.bytes < 16 || f.tile_bytes == 0 || f.tile_bytes % 16 || f.ntiles != l.nblocks ||
+        if (!unpack || !f.base || f.bytes < 16 || f.tile_bytes < 16 || (f.tile_bytes & (f.tile_bytes - 1)) || f.ntiles != l.nblocks ||
             (f.bytes + f.tile_bytes - 1) / f.tile_bytes != f.ntiles)
             return false;
         c->prefetched_lo = c->prefetched_lo ? std::min(c->prefetched_lo, f.base) : f.base;
         c->prefetched_hi = std::max(c->prefetched_hi, f.base + f.bytes);
-        for (uint32_t b = 0; b < l.nblocks; ++b)
+        const uint32_t grid = l.grid ? l.grid : l.nblocks;
+        const int64_t loads_before = c->loads;
+        for (uint32_t b = 0; b < grid; ++b)
             for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t)
-                tp::prefetch_thread(f, b, t, HostMem{c});
+                tp::prefetch_thread(f, b, grid, t, HostMem{c});
+        // every 16-byte word of the bytes is loaded exactly once (the last may be pulled back)
+        if (c->loads - loads_before != static_cast<int64_t>((f.bytes + 15) / 16)) c->oob++;
         return true;
     }
     const tp::KParams p = tp::kernel_params(l);
