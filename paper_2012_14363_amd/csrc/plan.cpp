@@ -61,6 +61,7 @@ struct Splitter {
     int ur_short = 4;   // rows per thread in tiles for runs that fit the workgroup
     int nt = 3;         // streaming hints of the launches
     uint32_t grid = 0;  // workgroups per launch (0 = one per tile)
+    int64_t chunk_rows = 0;  // > 0: no launch of more rows (staged unpack)
 
     int64_t word() const { return int64_t{1} << word_log2; }
     // Words that cover a run of `bytes` (>= one word): the last one may overlap its neighbour.
@@ -107,7 +108,8 @@ struct Splitter {
         const int64_t br = kBlockThreads >> probe.p.bx_log2;
         const int64_t nxc = (n0 + bx * probe.ux - 1) / (bx * probe.ux);
         const int64_t by_blocks = ((int64_t{1} << 30) / nxc) * br * probe.ur;
-        return std::max<int64_t>(1, std::min(in.max_rows_per_launch, by_blocks));
+        const int64_t limit = std::min(in.max_rows_per_launch, by_blocks);
+        return std::max<int64_t>(1, chunk_rows > 0 ? std::min(limit, chunk_rows) : limit);
     }
 
     // Rows: split the outermost dimension until a launch's row count fits.
@@ -266,12 +268,18 @@ bool plan_xpose(const PlanInput& in, const std::vector<Dim>& dims, const char* t
 // read-only pass that brings its packed bytes into L2 followed by the store passes, all with the
 // same few workgroups taking the same tiles: workgroup ids map to XCDs round-robin, so a tile's
 // bytes wait in the L2 its stores will ask.  Returns false where this does not apply.
-bool plan_staged(const PlanInput& in, const std::vector<Dim>& dims, const char* typed, std::vector<Launch>* out) {
-    if (dims.size() != 2) return false;
-    const int64_t run = dims[0].count, rows = dims[1].count, pitch = dims[1].stride;
+bool plan_staged(const PlanInput& in, const std::vector<Dim>& all_dims, const char* typed, std::vector<Launch>* out) {
+    std::vector<Dim> dims = {all_dims[0]};
+    for (size_t d = 1; d < all_dims.size(); ++d)
+        if (all_dims[d].count != 1) dims.push_back(all_dims[d]);   // a dimension of one row is none
+    if (dims.size() < 2) return false;
+    const int64_t run = dims[0].count, pitch = dims[1].stride;
+    int64_t rows = 1;
+    for (size_t d = 1; d < dims.size(); ++d) rows *= dims[d].count;
     const int64_t step = pitch < 0 ? -pitch : pitch;
     if (run > 16 || (run & (run - 1)) != 0 || (int64_t{1} << in.max_word_log2) < run) return false;
     if (step != 128 && step != 256 && step != 512) return false;
+    if (dims.size() > 2 && step != 512) return false;   // passes over every 2nd or 4th row: one row dimension only
     if (in.stage != 1 && rows < kStagedRows) return false;
     if (in.max_rows_per_launch != (int64_t{1} << 30) || in.max_words_per_run != (int64_t{1} << 30)) return false;
     const int64_t passes = 512 / step;
@@ -285,19 +293,33 @@ bool plan_staged(const PlanInput& in, const std::vector<Dim>& dims, const char* 
     const uint32_t grid = in.stage_grid > 0 ? static_cast<uint32_t>(in.stage_grid) : kStagedGrid;
     int word_log2 = 0;
     while ((int64_t{1} << word_log2) < run) ++word_log2;
-    for (int64_t lo = 0; lo < rows; lo += chunk_rows) {
-        const int64_t n = std::min(chunk_rows, rows - lo);
-        if (n * run >= 16) {
-            Launch l;
-            l.kind = kPrefetch;
-            l.f.base = in.packed + lo * run;
-            l.f.bytes = static_cast<uint64_t>(n * run);
-            l.f.tile_bytes = static_cast<uint32_t>(tile_rows * run);
-            l.f.ntiles = static_cast<uint32_t>((n + tile_rows - 1) / tile_rows);
-            l.nblocks = l.f.ntiles;
-            l.grid = std::min(grid, l.nblocks);
+    auto add_prefetch = [&](const char* base, int64_t nrows) {
+        if (nrows * run < 16) return;   // the read-only pass loads 16-byte words
+        Launch l;
+        l.kind = kPrefetch;
+        l.f.base = base;
+        l.f.bytes = static_cast<uint64_t>(nrows * run);
+        l.f.tile_bytes = static_cast<uint32_t>(tile_rows * run);
+        l.f.ntiles = static_cast<uint32_t>((nrows + tile_rows - 1) / tile_rows);
+        l.nblocks = l.f.ntiles;
+        l.grid = std::min(grid, l.nblocks);
+        out->push_back(l);
+    };
+    if (dims.size() > 2) {
+        // several row dimensions (512-byte pitch, one pass): the splitter cuts the outer dimensions into
+        // launches of at most a chunk's rows, consecutive in the packed stream; each gets its pass in front
+        std::vector<Launch> cut;
+        Splitter s{in, word_log2, run, &cut, 1, in.nt >= 0 ? in.nt : 6, grid, chunk_rows};
+        s.split_rows(dims, typed, in.packed);
+        for (const Launch& l : cut) {
+            add_prefetch(l.p.packed, static_cast<int64_t>(l.p.nrows));
             out->push_back(l);
         }
+        return true;
+    }
+    for (int64_t lo = 0; lo < rows; lo += chunk_rows) {
+        const int64_t n = std::min(chunk_rows, rows - lo);
+        add_prefetch(in.packed + lo * run, n);
         for (int64_t p = 0; p < passes && p < n; ++p) {
             // rows lo + p, lo + p + passes, ...: `passes` rows apart on both sides
             Splitter s{in, word_log2, run * passes, out, 1, in.nt >= 0 ? in.nt : 6, grid};

@@ -386,14 +386,22 @@ def test_emulated_staged_unpack_of_tiny_rows():
     assert res["unpack_plan"].count("prefetch") == 1 and res["unpack_plan"].count("tile W=1") == 4
     # where it does not apply: rows of several words, other pitches, more row dimensions, too few rows unless forced
     for t in (vector(3000, 3, 512, BYTE), vector(3000, 4, 384, BYTE), vector(3000, 32, 512, BYTE), vector(3000, 4, 1024, BYTE),
-              vector(3000, 8, 256, BYTE), vector(3000, 2, 128, BYTE), hvector(3, 1, 1 << 20, vector(1000, 4, 512, BYTE))):
+              vector(3000, 8, 256, BYTE), vector(3000, 2, 128, BYTE), hvector(3, 1, 1 << 20, vector(1000, 4, 256, BYTE))):
         assert "prefetch" not in _emulate_roundtrip(t, 1, stage=1)["unpack_plan"], t
     assert "prefetch" not in _emulate_roundtrip(vector(5000, 1, 512, BYTE), 1)["unpack_plan"]
     assert "prefetch" not in _emulate_roundtrip(vector(5000, 1, 512, BYTE), 1, stage=0)["unpack_plan"]
     # objects that abut fold into rows and are staged together; objects apart are an outer dimension
     res = _emulate_roundtrip(subarray((512, 512), (512, 4), (0, 0), "C", BYTE), 3, stage=1)
     assert "prefetch bytes=6144 " in res["unpack_plan"] and " rows=1536 " in res["unpack_plan"]
-    assert "prefetch" not in _emulate_roundtrip(vector(512, 4, 512, BYTE), 3, stage=1)["unpack_plan"]
+    # several row dimensions at 512-byte pitch: the outer dimensions are cut into chunks, each with its pass in front
+    res = _emulate_roundtrip(hvector(5, 1, 1 << 20, vector(1000, 4, 512, BYTE)), 1, stage=1, stage_bytes=8192, typed_shift=2, position=1)
+    lines = res["unpack_plan"].splitlines()
+    assert len(lines) == 6 and lines[0] == "prefetch bytes=8000 tile=1024 blocks=8 grid=8", lines
+    assert lines[1].startswith("tile W=4 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=2000 nrd=2 ") and lines[1].endswith(" grid=8"), lines
+    assert lines[4] == "prefetch bytes=4000 tile=1024 blocks=4 grid=4" and " rows=1000 nrd=1 " in lines[5], lines
+    assert res["unpack_prefetched_span"] == 20000
+    res = _emulate_roundtrip(vector(512, 4, 512, BYTE), 3, stage=1)     # three objects apart: an outer dimension
+    assert res["unpack_plan"].count("prefetch") == 1 and " rows=1536 nrd=2 " in res["unpack_plan"]
 
 
 def test_emulated_ragged_runs_at_any_alignment():
