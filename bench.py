@@ -71,26 +71,26 @@ def sector_bound_fraction(run: int, granule: int = 128) -> float:
 # Keyed by (op, a0): (bytes fetched, bytes written), per call (a staged unpack is 8 launches; its store passes
 # fetch the packed bytes a second time under the profiler, which starts every dispatch with a cold L2).
 MEASURED_TRAFFIC = {
-    ('pack', 1): (8585954523, 72397743),
-    ('pack', 2): (4293047948, 72013875),
-    ('pack', 4): (2146545596, 70380851),
-    ('pack', 8): (1073285464, 66985443),
-    ('pack', 16): (536667616, 67017896),
-    ('pack', 32): (268346282, 67020579),
-    ('pack', 64): (134189325, 67094682),
-    ('pack', 128): (67110015, 67056097),
-    ('pack', 256): (67109888, 67090977),
+    ('pack', 1): (8585927399, 72465796),
+    ('pack', 2): (4293037841, 72037175),
+    ('pack', 4): (2146547131, 70435217),
+    ('pack', 8): (1073279835, 67041093),
+    ('pack', 16): (536660963, 67062959),
+    ('pack', 32): (268343084, 67070631),
+    ('pack', 64): (134187790, 67136228),
+    ('pack', 128): (67110015, 67112189),
+    ('pack', 256): (67109888, 67105028),
     ('pack', 512): (67108864, 67108864),
-    ('unpack', 1): (134428572, 2143534189),
-    ('unpack', 2): (134428572, 1071767094),
-    ('unpack', 4): (134428572, 535883547),
-    ('unpack', 8): (134387632, 267941774),
-    ('unpack', 16): (134428572, 133970887),
-    ('unpack', 32): (67100676, 66985443),
-    ('unpack', 64): (67102723, 66985443),
-    ('unpack', 128): (67109888, 67091488),
-    ('unpack', 256): (67110015, 67071173),
-    ('unpack', 512): (67108864, 67039105),
+    ('unpack', 1): (134428572, 2145306785),
+    ('unpack', 2): (134428572, 1072653392),
+    ('unpack', 4): (134428572, 536326696),
+    ('unpack', 8): (134387632, 268163348),
+    ('unpack', 16): (134428572, 134081674),
+    ('unpack', 32): (67100676, 67040837),
+    ('unpack', 64): (67102723, 67040837),
+    ('unpack', 128): (67110015, 67128300),
+    ('unpack', 256): (67109888, 67101448),
+    ('unpack', 512): (67108864, 67110910),
 }
 
 
