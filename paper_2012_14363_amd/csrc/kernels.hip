@@ -18,6 +18,10 @@
 //     the (run-time constant) dimension counts; in the tiles for long runs the row
 //     is uniform across the workgroup and that math runs on the scalar unit;
 //   * all parameters arrive by value in the kernel-argument segment.
+//
+// Beside it: the transposing kernel (tiles through LDS), the batched kernel (many
+// planned launches as one grid) and the read-only pass of a staged unpack, which
+// brings packed bytes into L2 ahead of the stores that consume them.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
