@@ -210,7 +210,8 @@ def main():
     if dominant["op"] == "unpack" and dominant["a"][0] < 64:
         roofline["note"] = ("one call = `launches_per_call` launches on the stream (per 16 MiB chunk a read-only pass that "
                             "brings the packed bytes into L2, then the store pass); `avg_launch_us`, `achieved` and "
-                            "`traffic` are per call, all launches included.  Hardware-bound: every row leaves L2 as one "
+                            "`traffic` are per call, all launches included (`traffic` holds the packed bytes twice: counter collection "
+                            "starts every dispatch with a cold L2, so there the store passes fetch them again).  Hardware-bound: every row leaves L2 as one "
                             "masked 32-byte write and is read-modify-written beyond L2, where the L2-side counters in "
                             "`traffic` do not see it; such rows retire at about 24 G/s in general and at about 37 G/s in "
                             "this staged form (rows 512 bytes apart, no read from HBM between the writes)")
