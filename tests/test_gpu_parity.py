@@ -182,6 +182,10 @@ def test_ragged_runs_at_any_alignment(dev, run):
         tp.set_override("word", 0)
 
 
+def dev_base_mod_512(dev):
+    return torch.empty(1 << 20, dtype=torch.uint8, device=dev).data_ptr() % 512
+
+
 def test_staged_unpack_of_tiny_rows(dev):
     # a million rows or more of one word each at 512-, 256- or 128-byte pitch: per 16 MiB of packed bytes a
     # read-only pass and store passes over rows 512 bytes apart; exact bytes, gaps untouched, any addresses
@@ -195,6 +199,9 @@ def test_staged_unpack_of_tiny_rows(dev):
         assert plans["unpack"].count("prefetch") == chunks, plans["unpack"]
         assert plans["unpack"].count(f"tile W={run} ux=1 ur=1 nt=6 ") == chunks * passes, plans["unpack"]
         assert "prefetch" not in plans["pack"]
+    # rows in the last line of their 512-byte block are left unstaged (no gain there); torch aligns its blocks to 512
+    plans = roundtrip(vector((1 << 20) + 5, 8, 512, BYTE), 1, dev, typed_shift=330, seed=8)
+    assert (dev_base_mod_512(dev) + 64 + 330) % 512 >= 384 and "prefetch" not in plans["unpack"] and "nt=7" in plans["unpack"]
     # three row dimensions at 512-byte pitch, two objects apart
     say("staged unpack, 3D")
     plans = roundtrip(hvector(40, 1, 300 * 512 + 64, vector(300, 8, 512, BYTE)), 90, dev, typed_shift=4, position=3, seed=9)
