@@ -395,7 +395,7 @@ int plan_launches(const PlanInput& in, std::vector<Launch>* out) {
     const bool own_launch = !in.batched || rows >= kSoloRows || rows * run >= kSoloBytes;
     if (in.unpack && !in.packed_on_host && in.unpack_rule == 1 && in.narrow_partial_rows && partial_rows &&
         inner_pitch < kPageBytes && outer_pitch >= kLineBytes && own_launch) {
-        if (in.stage != 0 && !in.batched && plan_staged(in, dims, typed, out)) return kSuccess;
+        if (in.stage != 0 && plan_staged(in, dims, typed, out)) return kSuccess;
         // Rows that end in partially written memory lines, follow one another closer than a page and
         // share no line with rows of another outer index (those L2 should keep and merge): their
         // stores are written through L2 at once (`sc1 nt`) rather than left for eviction, a thread

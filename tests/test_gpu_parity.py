@@ -692,7 +692,8 @@ def test_batch_unpack_large_requests_take_their_own_launch(dev):
     # a launch of their own (one row per thread, sc1 nt stores); the bytes are the oracle's either way
     reqs, typed_len = [], 0
     for t in (vector(300, 24, 64, BYTE), vector((1 << 20) + 5, 3, 16, BYTE), vector(100, 200, 512, BYTE),
-              vector(45000, 200, 512, BYTE), hvector(7, 1, 5000, vector(40, 10, 100, BYTE))):
+              vector(45000, 200, 512, BYTE), hvector(7, 1, 5000, vector(40, 10, 100, BYTE)),
+              vector((1 << 20) + 9, 4, 512, BYTE)):
         d, n = cc.blocks(t, 1)
         origin = typed_len + 1
         typed_len = origin + int((d + n).max()) + 16
@@ -707,6 +708,7 @@ def test_batch_unpack_large_requests_take_their_own_launch(dev):
     assert tp.unpack_batch(packed, total + 3, 3, bb) == total + 3
     plan = tp.last_plan()
     assert plan.count("batch") == 1 and plan.count("ur=1 nt=7") == 2 and "rows=1048581" in plan and "rows=45000" in plan, plan
+    assert plan.count("prefetch") == 1 and "tile W=4 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=1048585 " in plan, plan   # and staged
     want = np.full(typed_len, 0xA5, np.uint8)
     pos = 3
     for t, c, o in reqs:
