@@ -772,6 +772,35 @@ def test_async_calls_replay_from_a_hip_graph(dev):
         assert np.array_equal(packed.cpu().numpy(), expect)
 
 
+def test_staged_unpack_replays_from_a_hip_graph(dev):
+    # a staged unpack is several launches (read-only passes and store passes): captured once, it replays
+    # with new packed bytes each time
+    rows, run, pitch = (1 << 20) + 700, 4, 256
+    t = vector(rows, run, pitch, BYTE)
+    h = tp.type_from_recipe(t)
+    size = rows * run
+    packed = torch.zeros(size, dtype=torch.uint8, device=dev)
+    typed = torch.full((rows * pitch + 64,), 0xA5, dtype=torch.uint8, device=dev)
+    side = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    say("capture a staged unpack")
+    torch.cuda.synchronize()
+    with torch.cuda.graph(g, stream=side):
+        assert tp.unpack_async(packed, size, 0, typed.data_ptr() + 8, 1, h, torch.cuda.current_stream()) == size
+    assert tp.last_plan().count("prefetch") == 1 and tp.last_plan().count("tile W=4 ux=1 ur=1 nt=6") == 2, tp.last_plan()
+    for rep in range(3):
+        say("replay", rep)
+        packed_h = W.random_bytes(900 + rep, size)
+        packed.copy_(torch.from_numpy(packed_h))     # eager work between replays
+        typed.fill_(0xA5)
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        want = np.full(rows * pitch + 64, 0xA5, np.uint8)
+        cc.unpack(packed_h, 0, want, 8, 1, t)
+        assert np.array_equal(typed.cpu().numpy(), want)
+
+
 # ------------------------------------------------------------------ model and host delivery
 def test_model_measure_and_host_delivery(dev, tmp_path):
     from oracle import model as om
