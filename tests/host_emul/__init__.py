@@ -153,7 +153,7 @@ def transfer(unpack, block, extent, count, typed, origin, packed, position, *, m
     arr = ctypes.c_int64 * nd
     dst = typed if unpack else packed
     wc = np.zeros(dst.size, dtype=np.uint8) if count_writes else None
-    result = (ctypes.c_int64 * 6)()
+    result = (ctypes.c_int64 * 7)()
     text = ctypes.create_string_buffer(1 << 16)
     rc = _load().emul_transfer(int(unpack), nd, start, arr(*counts), arr(*strides), extent, count,
                                typed.ctypes.data, typed.size, origin, packed.ctypes.data, packed.size, position,
@@ -161,7 +161,8 @@ def transfer(unpack, block, extent, count, typed, origin, packed, position, *, m
                                int(allow_xpose), stage, stage_bytes, wc.ctypes.data if wc is not None else None, result,
                                text, len(text))
     return {"rc": rc, "oob": result[0], "unaligned": result[1], "rewritten": result[2], "launches": result[3],
-            "duplicates": result[4], "prefetched_span": result[5], "plan": text.value.decode(), "write_count": wc}
+            "duplicates": result[4], "prefetched_span": result[5], "misplaced": result[6], "plan": text.value.decode(),
+            "write_count": wc}
 
 
 def transfer_batch(unpack, requests, typed, packed, position, count_writes=True):

@@ -33,6 +33,12 @@ struct Checks {
     int64_t loads = 0;      // all loads
     const char* prefetched_lo = nullptr;  // what the read-only passes of a staged unpack cover
     const char* prefetched_hi = nullptr;
+    // staged unpack: the last read-only pass, and the tile a store pass is in; a packed byte read by
+    // tile t of a store pass must lie in tile t of that read-only pass (same workgroup, same XCD's L2)
+    tp::PrefetchParams pass{};
+    bool in_store_pass = false;
+    uint32_t tile = 0;
+    int64_t misplaced = 0;
 };
 
 struct HostMem {
@@ -44,6 +50,10 @@ struct HostMem {
     W load(const char* p) const {
         W v{};
         c->loads++;
+        if (c->in_store_pass && p >= c->packed_lo && p < c->packed_hi) {
+            const char* lo = c->pass.base + static_cast<uint64_t>(c->tile) * c->pass.tile_bytes;
+            if (c->pass.base == nullptr || p < lo || p + sizeof(W) > lo + c->pass.tile_bytes) c->misplaced++;
+        }
         if (!inside(p, sizeof(W))) { c->oob++; return v; }
         if (reinterpret_cast<uintptr_t>(p) % sizeof(W)) c->unaligned++;
         std::memcpy(&v, p, sizeof(W));
@@ -74,9 +84,11 @@ struct RunLaunch {
     HostMem mem;
     template <int WLOG2, int UX, int UR, int NRD>
     void operator()() {
-        for (uint32_t b = 0; b < nblocks; ++b)
+        for (uint32_t b = 0; b < nblocks; ++b) {
+            mem.c->tile = b;
             for (uint32_t t = 0; t < static_cast<uint32_t>(tp::kBlockThreads); ++t)
                 tp::tile_thread<WLOG2, UX, UR, UNPACK, NRD>(*p, b, t, mem);
+        }
     }
 };
 
@@ -130,6 +142,8 @@ bool run_launch(const tp::Launch& l, bool unpack, Checks* c) {
         if (!unpack || !f.base || f.bytes < 16 || f.tile_bytes < 16 || (f.tile_bytes & (f.tile_bytes - 1)) || f.ntiles != l.nblocks ||
             (f.bytes + f.tile_bytes - 1) / f.tile_bytes != f.ntiles)
             return false;
+        c->pass = f;
+        c->in_store_pass = false;
         c->prefetched_lo = c->prefetched_lo ? std::min(c->prefetched_lo, f.base) : f.base;
         c->prefetched_hi = std::max(c->prefetched_hi, f.base + f.bytes);
         const uint32_t grid = l.grid ? l.grid : l.nblocks;
@@ -142,6 +156,10 @@ bool run_launch(const tp::Launch& l, bool unpack, Checks* c) {
         return true;
     }
     const tp::KParams p = tp::kernel_params(l);
+    // a launch on few workgroups behind a read-only pass is one of its store passes (a chunk of fewer
+    // than 16 bytes has no such pass in front)
+    c->in_store_pass = unpack && l.grid != 0 && c->pass.base != nullptr &&
+                       p.packed >= c->pass.base && p.packed < c->pass.base + c->pass.bytes;
     if (unpack) {
         RunLaunch<true> run{&p, l.nblocks, HostMem{c}};
         return tp::dispatch_launch(l, p.nrd, run);
@@ -203,6 +221,7 @@ int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, c
     result[3] = static_cast<int64_t>(launches.size());
     result[4] = c.duplicates;
     result[5] = c.prefetched_hi - c.prefetched_lo;   // span of the packed bytes the read-only passes cover
+    result[6] = c.misplaced;
     return 0;
 }
 

@@ -277,6 +277,8 @@ def _emulate_roundtrip(t, incount, *, typed_shift=0, packed_shift=0, position=0,
         dst[:] = 0xA5
         back = host_emul.transfer(True, block, ex, incount, dst, origin, packed, position, **kw)
         assert back["rc"] == 0 and back["oob"] == 0 and back["rewritten"] == 0, (t, back)
+        # staged unpack: every store pass reads its packed bytes from the tile of the same index of the read-only pass
+        assert back["misplaced"] == 0, (t, back["plan"])
         want = np.full(n, 0xA5, dtype=np.uint8)
         cc.unpack(packed, position, want, origin, incount, t)
         assert np.array_equal(dst, want), (t, back["plan"])
