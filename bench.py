@@ -365,6 +365,32 @@ def extras(W, tp, torch, np, dev, stream):
                 tp.set_override("unpack_rule", 1)
         res[f"rows_of_{run}B_at_512B_pitch_48MiB"] = entry
         del typed_o
+    # unpack of 2^24 tiny rows at 512-byte pitch from twelve rotating sources: as planned (staged: packed bytes
+    # brought into L2 per 16 MiB, stores written through, rows 512 bytes apart), written through but not
+    # staged, and with plain streaming stores, four rows per thread
+    rows_t = 1 << 24
+    typed_t = torch.empty(rows_t * 512, dtype=torch.uint8, device=dev).fill_(1)
+    entry = {}
+    for run in (1, 4):
+        t_t = tp.type_from_recipe(W.vector(rows_t, run, 512, W.BYTE))
+
+        def un_t():
+            j = k[0] % 12
+            tp.unpack_async(dsts[j], rows_t * run, 0, typed_t, 1, t_t, stream)
+            k[0] += 1
+        one = {"staged_us": round(timed(un_t, n=10), 1)}
+        try:
+            tp.set_override("stage", 0)
+            one["written_through_us"] = round(timed(un_t, n=10), 1)
+            tp.set_override("unpack_rule", 0)
+            one["streaming_stores_us"] = round(timed(un_t, n=10), 1)
+        finally:
+            tp.set_override("stage", -1)
+            tp.set_override("unpack_rule", 1)
+        one["staged_rows_per_ns"] = round(rows_t / one["staged_us"] / 1e3, 2)
+        entry[f"{run}B_rows"] = one
+    res["unpack_2p24_tiny_rows_at_512B_pitch"] = entry
+    del typed_t
     del srcs, dsts
 
     # the runtime's own 2D copy (the DMA-engine route the paper lists as future work, Sec. 8) on the
