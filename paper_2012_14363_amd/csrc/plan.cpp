@@ -15,6 +15,7 @@ constexpr int64_t kLineBytes = 128;   // memory line: what a partial write is re
 constexpr int64_t kSoloRows = int64_t{1} << 20, kSoloBytes = int64_t{8} << 20;  // batch requests worth their own launch
 constexpr int64_t kStagedRows = int64_t{1} << 20;  // fewer rows do not repay the extra passes of a staged unpack
 constexpr uint32_t kStagedGrid = 256;              // workgroups of a staged launch: one per compute unit
+constexpr uint32_t kPrefetchGridFactor = 8;        // the read-only pass takes that many times more
 
 struct Dim {
     int64_t count;
@@ -307,7 +308,9 @@ bool plan_staged(const PlanInput& in, const std::vector<Dim>& all_dims, const ch
         l.f.tile_bytes = static_cast<uint32_t>(tile_rows * run);
         l.f.ntiles = static_cast<uint32_t>((nrows + tile_rows - 1) / tile_rows);
         l.nblocks = l.f.ntiles;
-        l.grid = std::min(grid, l.nblocks);
+        // more workgroups than the store passes have (the read is over sooner), still a multiple of the
+        // eight XCDs, so tile t lands on XCD t mod 8 here as there
+        l.grid = std::min(grid * kPrefetchGridFactor, l.nblocks);
         out->push_back(l);
     };
     if (dims.size() > 2) {
