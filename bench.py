@@ -71,26 +71,26 @@ def sector_bound_fraction(run: int, granule: int = 128) -> float:
 # Keyed by (op, a0): (bytes fetched, bytes written), per call (a staged unpack is 8 launches; its store passes
 # fetch the packed bytes a second time under the profiler, which starts every dispatch with a cold L2).
 MEASURED_TRAFFIC = {
-    ('pack', 1): (8585927399, 72465796),
-    ('pack', 2): (4293037841, 72037175),
-    ('pack', 4): (2146547131, 70435217),
-    ('pack', 8): (1073279835, 67041093),
-    ('pack', 16): (536660963, 67062959),
-    ('pack', 32): (268343084, 67070631),
-    ('pack', 64): (134187790, 67136228),
-    ('pack', 128): (67110015, 67112189),
-    ('pack', 256): (67109888, 67105028),
+    ('pack', 1): (8585928167, 72372662),
+    ('pack', 2): (4293036945, 72147685),
+    ('pack', 4): (2146543293, 70406579),
+    ('pack', 8): (1073277660, 67056553),
+    ('pack', 16): (536661731, 67077912),
+    ('pack', 32): (268345515, 67077273),
+    ('pack', 64): (134188942, 67125235),
+    ('pack', 128): (67110143, 67113468),
+    ('pack', 256): (67110143, 67106562),
     ('pack', 512): (67108864, 67108864),
-    ('unpack', 1): (134428572, 2145306785),
-    ('unpack', 2): (134428572, 1072653392),
-    ('unpack', 4): (134428572, 536326696),
-    ('unpack', 8): (134387632, 268163348),
-    ('unpack', 16): (134428572, 134081674),
-    ('unpack', 32): (67100676, 67040837),
-    ('unpack', 64): (67102723, 67040837),
-    ('unpack', 128): (67110015, 67128300),
-    ('unpack', 256): (67109888, 67101448),
-    ('unpack', 512): (67108864, 67110910),
+    ('unpack', 1): (134428572, 2145809690),
+    ('unpack', 2): (134428572, 1072904845),
+    ('unpack', 4): (134428572, 536452422),
+    ('unpack', 8): (134387632, 268226211),
+    ('unpack', 16): (134428572, 134113106),
+    ('unpack', 32): (67100676, 67056553),
+    ('unpack', 64): (67102723, 67056553),
+    ('unpack', 128): (67109888, 67163094),
+    ('unpack', 256): (67110015, 67134316),
+    ('unpack', 512): (67108864, 67132653),
 }
 
 
