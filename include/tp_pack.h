@@ -132,7 +132,10 @@ int tp_pack_size(int incount, tp_type t, int64_t *size);
  *
  * tp_pack / tp_unpack return after the data is complete (they synchronize the stream, as the
  * paper's timed region does, Sec. 6.3).  The *_async forms only enqueue on the stream; the
- * caller synchronizes.
+ * caller synchronizes.  A call may enqueue several kernels (a very large request is split; an
+ * unpack of a million or more tiny rows alternates read-only passes over its packed bytes with
+ * the passes that store them), all on `hip_stream` and in order; none allocates or records a
+ * memset, so a stream capture of the *_async forms replays from a HIP graph.
  */
 int tp_pack(const void *inbuf, int incount, tp_type t, void *outbuf, int64_t outsize, int64_t *position,
             void *hip_stream);
