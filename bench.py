@@ -270,7 +270,7 @@ def cpu_baseline(W, np):
         for p, o in zip(pts, outs):
             cc.unpack(o, 0, src, 0, 1, p["recipe"], nthreads=cores)
         reps += 1
-        if time.perf_counter() - t0 > 10.0 or reps >= 20:
+        if time.perf_counter() - t0 > 8.0:
             break
     dt = time.perf_counter() - t0
     moved = reps * sum(2 * p["packed_bytes"] for p in pts) * 2
