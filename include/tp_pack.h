@@ -133,7 +133,7 @@ int tp_pack_size(int incount, tp_type t, int64_t *size);
  * tp_pack / tp_unpack return after the data is complete (they synchronize the stream, as the
  * paper's timed region does, Sec. 6.3).  The *_async forms only enqueue on the stream; the
  * caller synchronizes.  A call may enqueue several kernels (a very large request is split; an
- * unpack of a million or more tiny rows alternates read-only passes over its packed bytes with
+ * unpack of half a million or more tiny rows alternates read-only passes over its packed bytes with
  * the passes that store them), all on `hip_stream` and in order; none allocates or records a
  * memset, so a stream capture of the *_async forms replays from a HIP graph.
  */
@@ -275,7 +275,7 @@ int tp_resource_stats(int kind, tp_resource_counts *out);
  *                   memory lines in narrow words (measured faster) rather than the widest
  *   "unpack_rule"   "1" (default) or "0": 0 plans such rows as before write-through stores
  *                   (4- or 8-byte words, four rows per thread), for comparisons
- *   "stage"         "-1" (automatic: from 2^20 rows), "0" (never) or "1" (wherever it applies): staged
+ *   "stage"         "-1" (automatic: from 2^19 rows), "0" (never) or "1" (wherever it applies): staged
  *                   unpack of rows of one word at 512-, 256- or 128-byte pitch (a read-only pass per chunk
  *                   of packed bytes, then the stores); "stage_bytes" 4096 .. 2^30: packed bytes per chunk
  *                   (default 16 MiB); "stage_grid" "0" (automatic) or the workgroups of such a launch
