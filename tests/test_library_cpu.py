@@ -392,6 +392,11 @@ def test_emulated_staged_unpack_of_tiny_rows():
         assert "prefetch" not in _emulate_roundtrip(t, 1, stage=1)["unpack_plan"], t
     assert "prefetch" not in _emulate_roundtrip(vector(5000, 1, 512, BYTE), 1)["unpack_plan"]
     assert "prefetch" not in _emulate_roundtrip(vector(5000, 1, 512, BYTE), 1, stage=0)["unpack_plan"]
+    # left to itself the planner stages from 2^19 rows on (64 MiB of typed memory at 128-byte pitch)
+    res = _emulate_roundtrip(vector(1 << 19, 1, 128, BYTE), 1)
+    assert res["unpack_plan"].count("prefetch") == 1 and res["unpack_plan"].count("tile W=1 ux=1 ur=1 nt=6 ") == 4
+    assert " grid=256" in res["unpack_plan"] and "prefetch bytes=524288 tile=1024 blocks=512 grid=512" in res["unpack_plan"]
+    assert "prefetch" not in _emulate_roundtrip(vector((1 << 19) - 1, 1, 128, BYTE), 1)["unpack_plan"]
     # objects that abut fold into rows and are staged together; objects apart are an outer dimension
     res = _emulate_roundtrip(subarray((512, 512), (512, 4), (0, 0), "C", BYTE), 3, stage=1)
     assert "prefetch bytes=6144 " in res["unpack_plan"] and " rows=1536 " in res["unpack_plan"]
