@@ -11,9 +11,10 @@ step ends with one stream synchronize.  Inputs are resident in HBM before the
 timed region.  value = bytes read + bytes written by the method (2 x packed
 bytes per pack or unpack) / wall time.
 
-Prints ONE JSON line.  `roofline` is for the kernel that takes most of the step;
-`kernels` lists every point.  `cpu_baseline` is the CPU oracle on a bounded
-sample of the same sweep.
+The last line of stdout is ONE compact JSON object (below 2 KB): metric, value,
+ms_per_step, config, `roofline` for the call that takes most of the step, and
+`cpu_baseline`, the CPU oracle on a bounded sample of the same sweep.  Everything
+else (every sweep point, the secondary workloads) goes to the file --detail names.
 """
 from __future__ import annotations
 
@@ -32,7 +33,7 @@ HBM_PEAK_GBS = 8000.0
 PACKED_BYTES = 1 << 26
 
 
-def parse_args():
+def parse_args(argv=None):
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=30)
@@ -42,7 +43,12 @@ def parse_args():
                     help="planner override passed to tp_set_override (ablations), e.g. nt=0 or word=4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the secondary measurements")
-    return ap.parse_args()
+    ap.add_argument("--detail", default=os.path.join(ROOT, "gpurun_out", "bench_detail.json"),
+                    help="file that receives the full result (per-point table, secondary workloads)")
+    ap.add_argument("--points", default="", metavar="OP:A0,...",
+                    help="run only these calls of the sweep in the step, e.g. unpack:1,pack:32 (profiling runs; "
+                         "the printed value then is not the benchmark's)")
+    return ap.parse_args(argv)
 
 
 def summarise_plan(text: str):
@@ -65,37 +71,70 @@ def sector_bound_fraction(run: int, granule: int = 128) -> float:
     return 2.0 * run / (g * ((run + g - 1) // g) + run)
 
 
-# HBM bytes per launch of the sweep's kernels at 64 MiB packed, from rocprofv3 --pmc FETCH_SIZE and
-# WRITE_SIZE runs of this script (profiles/tile_kernel_strided_block_sweep_64MiB_hbm_traffic.md): counter KiB x 1024 x the
+# HBM bytes per call of the sweep's points at 64 MiB packed, from rocprofv3 --pmc FETCH_SIZE and WRITE_SIZE
+# runs of this script (profiles/tile_kernel_strided_block_sweep_64MiB_hbm_traffic.md): counter KiB x 1024 x the
 # factor a plain 64 MiB copy calibrates (FETCH_SIZE reads half the known bytes: x2; WRITE_SIZE: x1).
-# Keyed by (op, a0): (bytes fetched, bytes written), per call (a staged unpack is 8 launches; its store passes
-# fetch the packed bytes a second time under the profiler, which starts every dispatch with a cold L2).
+# Keyed by (op, a0): the plan the call had when the counters were read (tp_last_plan, summarised), bytes
+# fetched, bytes written.  A point whose plan differs today reports no traffic rather than a stale one.
 MEASURED_TRAFFIC = {
-    ('pack', 1): (8585928167, 72372662),
-    ('pack', 2): (4293036945, 72147685),
-    ('pack', 4): (2146543293, 70406579),
-    ('pack', 8): (1073277660, 67056553),
-    ('pack', 16): (536661731, 67077912),
-    ('pack', 32): (268345515, 67077273),
-    ('pack', 64): (134188942, 67125235),
-    ('pack', 128): (67110143, 67113468),
-    ('pack', 256): (67110143, 67106562),
-    ('pack', 512): (67108864, 67108864),
-    ('unpack', 1): (134428572, 2145809690),
-    ('unpack', 2): (134428572, 1072904845),
-    ('unpack', 4): (134428572, 536452422),
-    ('unpack', 8): (134387632, 268226211),
-    ('unpack', 16): (134428572, 134113106),
-    ('unpack', 32): (67100676, 67056553),
-    ('unpack', 64): (67102723, 67056553),
-    ('unpack', 128): (67109888, 67163094),
-    ('unpack', 256): (67110015, 67134316),
-    ('unpack', 512): (67108864, 67132653),
 }
 
 
-def main():
-    args = parse_args()
+def kernel_name(plan_line: str, op: str) -> str:
+    """The kernel instantiation a line of tp_last_plan() names, as rocprofv3 prints it (short form)."""
+    if plan_line.startswith("prefetch"):
+        return "prefetch_kernel"
+    if plan_line.startswith("xpose"):
+        return "xpose_kernel"
+    f = dict(kv.split("=") for kv in plan_line.split()[1:] if "=" in kv)
+    wlog2 = int(f["W"]).bit_length() - 1
+    nrd = int(f["nrd"])
+    nrd = 1 if nrd <= 1 else 2 if nrd == 2 else 0
+    return f"tile_kernel<{wlog2},{f['ux']},{f['ur']},{'true' if op == 'unpack' else 'false'},{nrd},{f['nt']}>"
+
+
+def kernels_of(plan_text: str, op: str) -> str:
+    names = []
+    for ln in plan_text.strip().splitlines():
+        n = kernel_name(ln, op)
+        if n not in names:
+            names.append(n)
+    return " + ".join(names)
+
+
+def cpu_model_string() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for ln in f:
+                if ln.lower().startswith("model name"):
+                    return ln.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+FINAL_KEYS = ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+              "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline")
+ROOFLINE_KEYS = ("bound", "kernel", "achieved", "peak", "unit", "frac", "avg_launch_us", "algorithmic_bytes_per_launch",
+                 "launches_per_call", "traffic", "traffic_rate_gbs", "limit")
+CPU_KEYS = ("value", "unit", "cores", "cpu_model", "kind", "single_thread_value", "sample")
+
+
+def final_line(out: dict) -> str:
+    """The one line the benchmark ends with: the contract's keys only, everything long left to the detail file."""
+    line = {k: out[k] for k in FINAL_KEYS if k in out}
+    line["roofline"] = {k: out["roofline"][k] for k in ROOFLINE_KEYS if k in out["roofline"]}
+    if "cpu_baseline" in out:
+        line["cpu_baseline"] = {k: out["cpu_baseline"][k] for k in CPU_KEYS if k in out["cpu_baseline"]}
+    if "detail" in out:
+        line["detail"] = out["detail"]
+    text = json.dumps(line, separators=(",", ":"))
+    assert len(text) < 2000, len(text)
+    return text
+
+
+def main(argv=None):
+    args = parse_args(argv)
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only; --gpus N with N > 1 is not supported "
               "(no collectives or sharding in this path).", file=sys.stderr)
@@ -115,6 +154,11 @@ def main():
 
     # ---------------------------------------------------------------- inputs, resident in HBM
     points = W.configs.cfg2_sweep(args.packed_bytes)
+    only = None
+    if args.points:
+        only = {(op, int(a0)) for op, _, a0 in (item.partition(":") for item in args.points.split(","))}
+        assert all(op in ("pack", "unpack") and a0 in W.configs.A0_SWEEP for op, a0 in only), args.points
+    runs = lambda op, p: only is None or (op, p["a"][0]) in only   # noqa: E731
     align = 1 << 21
     bases, total = [], 0
     for p in points:
@@ -132,12 +176,16 @@ def main():
         for i, p in enumerate(points):
             h = tp.type_from_recipe(p["recipe"])          # construct + commit
             handles.append(h)
+            if not runs("pack", p):
+                continue
             if events is not None:
                 events[0][i][0].record(stream)
             tp.pack_async(arena.data_ptr() + bases[i], 1, h, packed[i], p["packed_bytes"], 0, stream)
             if events is not None:
                 events[0][i][1].record(stream)
         for i, p in enumerate(points):
+            if not runs("unpack", p):
+                continue
             if events is not None:
                 events[1][i][0].record(stream)
             tp.unpack_async(packed[i], p["packed_bytes"], 0, arena.data_ptr() + bases[i], 1, handles[i], stream)
@@ -153,10 +201,13 @@ def main():
     plans = {"pack": [], "unpack": []}
     for i, p in enumerate(points):
         h = tp.type_from_recipe(p["recipe"])
-        tp.pack(arena.data_ptr() + bases[i], 1, h, packed[i], p["packed_bytes"], 0, stream)
-        plans["pack"].append(tp.last_plan().strip())
-        tp.unpack(packed[i], p["packed_bytes"], 0, arena.data_ptr() + bases[i], 1, h, stream)   # the bytes just packed
-        plans["unpack"].append(tp.last_plan().strip())
+        plans["pack"].append("")
+        plans["unpack"].append("")
+        if only is None or runs("pack", p) or runs("unpack", p):
+            tp.pack(arena.data_ptr() + bases[i], 1, h, packed[i], p["packed_bytes"], 0, stream)
+            plans["pack"][i] = tp.last_plan().strip()
+            tp.unpack(packed[i], p["packed_bytes"], 0, arena.data_ptr() + bases[i], 1, h, stream)   # the bytes just packed
+            plans["unpack"][i] = tp.last_plan().strip()
 
     def new_events():
         return [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in points]
@@ -171,26 +222,37 @@ def main():
     t1 = time.perf_counter()
 
     step_s = (t1 - t0) / args.steps
-    bytes_per_step = sum(2 * p["packed_bytes"] for p in points) * 2   # pack + unpack, read + write
+    ops = ("pack", "unpack")
+    bytes_per_step = sum(2 * p["packed_bytes"] for op in ops for p in points if runs(op, p))   # read + write
     value = bytes_per_step / step_s / 1e9
 
     # per-call device times from the HIP events recorded inside the timed region
+    use_traffic = args.packed_bytes == PACKED_BYTES and not args.override
     kernels = []
-    for d, op in enumerate(("pack", "unpack")):
+    for d, op in enumerate(ops):
         for i, p in enumerate(points):
+            if not runs(op, p):
+                continue
             ms = [all_events[k][d][i][0].elapsed_time(all_events[k][d][i][1]) for k in range(args.steps)]
             avg_us = 1e3 * sum(ms) / len(ms)
             srt = sorted(ms)
             alg = 2 * p["packed_bytes"]
             plan, nlaunch = summarise_plan(plans[op][i])
             run = p["a"][0] if p["a"][0] < 512 else p["packed_bytes"]
-            kernels.append({
-                "op": op, "a": list(p["a"]), "plan": plan, "launches_per_call": nlaunch, "avg_us": round(avg_us, 2),
+            k = {
+                "op": op, "a": list(p["a"]), "kernel": kernels_of(plans[op][i], op), "plan": plan,
+                "launches_per_call": nlaunch, "avg_us": round(avg_us, 2),
                 "median_us": round(1e3 * srt[len(srt) // 2], 2), "min_us": round(1e3 * srt[0], 2),
                 "algorithmic_bytes": alg, "gbs": round(alg / avg_us / 1e3, 1),
                 "frac_of_peak": round(alg / avg_us / 1e3 / HBM_PEAK_GBS, 4),
                 "sector_bound_frac_g128": round(sector_bound_fraction(run), 4),
-            })
+            }
+            m = MEASURED_TRAFFIC.get((op, p["a"][0]))
+            if m and use_traffic and m["plan"] == plan:   # HBM bytes actually moved, next to the algorithmic rate
+                k["hbm_traffic_fetch_write"] = [m["fetch"], m["write"]]
+                k["hbm_traffic_gbs"] = round((m["fetch"] + m["write"]) / avg_us / 1e3, 1)
+                k["hbm_traffic_frac_of_peak"] = round((m["fetch"] + m["write"]) / avg_us / 1e3 / HBM_PEAK_GBS, 4)
+            kernels.append(k)
     # the same-size plain copy through the same kernel (the dense a0 = 512 point) is the copy ceiling
     ceiling = {k["op"]: k["gbs"] for k in kernels if k["a"][0] == 512}
     for k in kernels:
@@ -198,35 +260,21 @@ def main():
             k["frac_of_copy_ceiling"] = round(k["gbs"] / ceiling[k["op"]], 4)
     dominant = max(kernels, key=lambda k: k["avg_us"])
     roofline = {
-        "bound": "hbm", "kernel": f"{dominant['op']} a={dominant['a']} [{dominant['plan']}]",
+        "bound": "hbm", "kernel": f"{dominant['kernel']} ({dominant['op']} a0={dominant['a'][0]})",
         "achieved": dominant["gbs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": round(dominant["gbs"] / HBM_PEAK_GBS, 4),
         "avg_launch_us": dominant["avg_us"], "algorithmic_bytes_per_launch": dominant["algorithmic_bytes"],
+        "launches_per_call": dominant["launches_per_call"],
         "traffic": None,
         "sector_bound_frac_g128": dominant["sector_bound_frac_g128"],
+        "plan": dominant["plan"],
     }
-    roofline["launches_per_call"] = dominant["launches_per_call"]
-    measured = MEASURED_TRAFFIC.get((dominant["op"], dominant["a"][0]))
-    if dominant["op"] == "unpack" and dominant["a"][0] < 64:
-        roofline["note"] = ("one call = `launches_per_call` launches on the stream (per 16 MiB chunk a read-only pass that "
-                            "brings the packed bytes into L2, then the store pass); `avg_launch_us`, `achieved` and "
-                            "`traffic` are per call, all launches included (`traffic` holds the packed bytes twice: counter collection "
-                            "starts every dispatch with a cold L2, so there the store passes fetch them again).  Hardware-bound: every row leaves L2 as one "
-                            "masked 32-byte write and is read-modify-written beyond L2, where the L2-side counters in "
-                            "`traffic` do not see it; such rows retire at about 24 G/s in general and at about 37 G/s in "
-                            "this staged form (rows 512 bytes apart, no read from HBM between the writes)")
-    use_traffic = args.packed_bytes == PACKED_BYTES and not args.override
-    if measured and use_traffic:
-        roofline["traffic"] = sum(measured)
-        roofline["traffic_fetch_write"] = list(measured)
-        roofline["traffic_rate_gbs"] = round(sum(measured) / dominant["avg_us"] / 1e3, 1)
-    if use_traffic:
-        for k in kernels:   # HBM bytes actually moved per second, next to the algorithmic rate
-            m = MEASURED_TRAFFIC.get((k["op"], k["a"][0]))
-            if m:
-                k["hbm_traffic_bytes"] = sum(m)
-                k["hbm_traffic_gbs"] = round(sum(m) / k["avg_us"] / 1e3, 1)
-                k["hbm_traffic_frac_of_peak"] = round(sum(m) / k["avg_us"] / 1e3 / HBM_PEAK_GBS, 4)
+    if dominant["launches_per_call"] > 1:
+        roofline["limit"] = "avg_launch_us, achieved and traffic are per call, all of its launches included"
+    if "hbm_traffic_fetch_write" in dominant:
+        roofline["traffic"] = sum(dominant["hbm_traffic_fetch_write"])
+        roofline["traffic_fetch_write"] = dominant["hbm_traffic_fetch_write"]
+        roofline["traffic_rate_gbs"] = dominant["hbm_traffic_gbs"]
 
     out = {
         "metric": "pack/unpack GB/s (read+write) and % of MI355X HBM peak; canonicalize us/type", "value": round(value, 2), "unit": "GB/s",
@@ -239,13 +287,22 @@ def main():
         "roofline": roofline,
         "kernels": kernels,
     }
+    if only is not None:
+        out["config"]["only"] = args.points
 
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(W, np)
     if not args.no_extras:
         out["extras"] = extras(W, tp, torch, np, dev, stream)
         out["other_workloads"] = other_workloads(W, tp, torch, arena, dev, stream)
-    print(json.dumps(out))
+    try:
+        os.makedirs(os.path.dirname(os.path.abspath(args.detail)), exist_ok=True)
+        with open(args.detail, "w") as f:
+            json.dump(out, f, indent=1)
+        out["detail"] = os.path.relpath(args.detail, ROOT)
+    except OSError as e:   # the detail file is a convenience; the line below is the result
+        print(f"bench.py: detail file not written: {e}", file=sys.stderr)
+    print(final_line(out), flush=True)
 
 
 def cpu_baseline(W, np):
@@ -280,8 +337,8 @@ def cpu_baseline(W, np):
     for p, o in zip(pts, outs):
         cc.unpack(o, 0, src, 0, 1, p["recipe"], nthreads=1)
     single = sum(2 * p["packed_bytes"] for p in pts) * 2 / (time.perf_counter() - t0) / 1e9
-    return {"value": round(moved / dt / 1e9, 3), "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "single_thread_value": round(single, 3),
+    return {"value": round(moved / dt / 1e9, 3), "unit": "GB/s", "cores": cores, "cpu_model": cpu_model_string(),
+            "kind": "oracle", "single_thread_value": round(single, 3),
             "sample": f"same sweep at 8 MiB packed per point (outermost dimension / 8), {reps} passes of "
                       f"pack+unpack over all 10 points, {cores} threads over the outermost loop"}
 

@@ -61,3 +61,59 @@ def test_bench_refuses_more_than_one_gpu():
                        text=True, timeout=120)
     assert r.returncode == 2
     assert "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_bench_final_line_is_compact_and_complete():
+    """The line the benchmark ends with must survive a reader that keeps only a few KB of stdout:
+    a result with everything long in it still formats to less than 2000 characters with the contract's keys."""
+    import json
+
+    import bench
+
+    long_plan = " + ".join(["4 x [tile W=1 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=16777216 nrd=1 blocks=65536 grid=256]"] * 6)
+    out = {
+        "metric": "pack/unpack GB/s (read+write) and % of MI355X HBM peak; canonicalize us/type", "value": 392.11,
+        "unit": "GB/s", "n_gpus": 1, "steps": 30, "warmup": 5, "ms_per_step": 6.8412, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": "3D strided-block sweep, a0 in {1..512}, 64 MiB packed per point, "
+                               "512x512xE2 byte allocation, pack+unpack of all 10 points per step",
+                   "packed_bytes_per_point": 1 << 26, "points": 10, "overrides": [], "bytes_per_step": 2684354560,
+                   "frac_of_hbm_peak": 0.049},
+        "roofline": {"bound": "hbm", "kernel": "prefetch_kernel + tile_kernel<0,1,1,true,1,6> (unpack a0=1)",
+                     "achieved": 75.6, "peak": 8000.0, "unit": "GB/s", "frac": 0.0095, "avg_launch_us": 1774.9,
+                     "algorithmic_bytes_per_launch": 134217728, "launches_per_call": 8, "traffic": 2280238262,
+                     "traffic_rate_gbs": 1284.7, "limit": "x" * 200, "plan": long_plan, "note": "y" * 3000},
+        "kernels": [{"plan": long_plan}] * 20, "extras": {"z": "w" * 20000}, "other_workloads": {"q": ["r" * 100] * 100},
+        "cpu_baseline": {"value": 4.012, "unit": "GB/s", "cores": 16, "cpu_model": "AMD EPYC 9575F 64-Core Processor",
+                         "kind": "oracle", "single_thread_value": 0.42, "sample": "s" * 180},
+        "detail": "gpurun_out/bench_detail.json",
+    }
+    line = bench.final_line(out)
+    assert len(line) < 2000 and "\n" not in line
+    got = json.loads(line)
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in got, key
+    assert got["config"]["workload"].startswith("3D strided-block sweep")
+    for key in ("bound", "kernel", "achieved", "peak", "unit", "frac", "avg_launch_us", "algorithmic_bytes_per_launch",
+                "launches_per_call", "traffic"):
+        assert key in got["roofline"], key
+    for key in ("value", "unit", "cores", "cpu_model", "kind", "sample"):
+        assert key in got["cpu_baseline"], key
+    assert "kernels" not in got and "extras" not in got and "other_workloads" not in got
+    assert abs(got["roofline"]["frac"] - got["roofline"]["achieved"] / got["roofline"]["peak"]) < 1e-3
+
+
+def test_bench_names_the_kernel_a_plan_line_runs():
+    import bench
+
+    assert bench.kernel_name("tile W=1 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=16777216 nrd=1 blocks=65536 grid=256",
+                             "unpack") == "tile_kernel<0,1,1,true,1,6>"
+    assert bench.kernel_name("tile W=16 ux=4 ur=1 nt=3 bx=256 n0=4194304 back=0 rows=1 nrd=0 blocks=4096",
+                             "pack") == "tile_kernel<4,4,1,false,1,3>"
+    assert bench.kernel_name("tile W=4 ux=1 ur=4 nt=3 bx=8 n0=6 back=0 rows=45 nrd=3 blocks=1", "pack") == \
+        "tile_kernel<2,1,4,false,0,3>"
+    assert bench.kernels_of("prefetch bytes=16777216 tile=256 blocks=65536 grid=2048\n"
+                            "tile W=1 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=16777216 nrd=1 blocks=65536 grid=256\n"
+                            "prefetch bytes=16777216 tile=256 blocks=65536 grid=2048\n", "unpack") == \
+        "prefetch_kernel + tile_kernel<0,1,1,true,1,6>"
