@@ -45,9 +45,10 @@ def parse_args(argv=None):
     ap.add_argument("--no-extras", action="store_true", help="skip the secondary measurements")
     ap.add_argument("--detail", default=os.path.join(ROOT, "gpurun_out", "bench_detail.json"),
                     help="file that receives the full result (per-point table, secondary workloads)")
-    ap.add_argument("--points", default="", metavar="OP:A0,...",
-                    help="run only these calls of the sweep in the step, e.g. unpack:1,pack:32 (profiling runs; "
-                         "the printed value then is not the benchmark's)")
+    ap.add_argument("--points", default="", metavar="OP:A0[@KEY=VALUE...],...",
+                    help="run only these calls of the sweep in the step, in this order, e.g. pack:32,unpack:1,unpack:1@stage=0 "
+                         "(profiling and ablation runs; a call's @overrides hold for that call only; the printed value "
+                         "then is not the benchmark's)")
     return ap.parse_args(argv)
 
 
@@ -78,6 +79,11 @@ def sector_bound_fraction(run: int, granule: int = 128) -> float:
 # fetched, bytes written.  A point whose plan differs today reports no traffic rather than a stale one.
 MEASURED_TRAFFIC = {
 }
+
+
+# what tp_set_override keys are reset to after a call that ran under its own overrides (--points ...@key=value)
+OVERRIDE_DEFAULTS = {"stage": -1, "unpack_rule": 1, "nt": -1, "word": 0, "ur": -1, "xpose": 1, "narrow_partial_rows": 1,
+                     "stage_bytes": 16 << 20, "stage_grid": 0}
 
 
 def kernel_name(plan_line: str, op: str) -> str:
@@ -147,71 +153,78 @@ def main(argv=None):
     from paper_2012_14363_amd import binding as tp
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.points:
+        args.no_extras = True   # the secondary workloads live in the full arena
     tp.lib()
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     stream = torch.cuda.current_stream()
 
-    # ---------------------------------------------------------------- inputs, resident in HBM
+    # ---------------------------------------------------------------- the step's calls
     points = W.configs.cfg2_sweep(args.packed_bytes)
-    only = None
+    # one call = (op, index of the sweep point, overrides in force for that call only)
     if args.points:
-        only = {(op, int(a0)) for op, _, a0 in (item.partition(":") for item in args.points.split(","))}
-        assert all(op in ("pack", "unpack") and a0 in W.configs.A0_SWEEP for op, a0 in only), args.points
-    runs = lambda op, p: only is None or (op, p["a"][0]) in only   # noqa: E731
+        calls = []
+        for item in args.points.split(","):
+            head, *ovr = item.split("@")
+            op, _, a0 = head.partition(":")
+            assert op in ("pack", "unpack") and int(a0) in W.configs.A0_SWEEP, item
+            assert all(kv.partition("=")[0] in OVERRIDE_DEFAULTS for kv in ovr), item
+            calls.append((op, W.configs.A0_SWEEP.index(int(a0)), tuple(kv.partition("=")[::2] for kv in ovr)))
+    else:
+        calls = [("pack", i, ()) for i in range(len(points))] + [("unpack", i, ()) for i in range(len(points))]
+    used = sorted({i for _, i, _ in calls})
+
+    # ---------------------------------------------------------------- inputs, resident in HBM
     align = 1 << 21
-    bases, total = [], 0
-    for p in points:
-        bases.append(total)
-        total += (p["alloc_bytes"] + align - 1) // align * align
+    bases, total = {}, 0
+    for i in used:
+        bases[i] = total
+        total += (points[i]["alloc_bytes"] + align - 1) // align * align
     arena = W.fills.counter_bytes_torch(W.configs.SEED_BASE + 1, total, dev)
-    packed = [torch.zeros(p["packed_bytes"], dtype=torch.uint8, device=dev) for p in points]
+    packed = {i: torch.zeros(points[i]["packed_bytes"], dtype=torch.uint8, device=dev) for i in used}
     torch.cuda.synchronize()
     for kv in args.override:
         key, _, val = kv.partition("=")
         tp.set_override(key, val)
 
+    def one_call(op, i, ovr, h, synchronous=False):
+        for key, val in ovr:
+            tp.set_override(key, val)
+        p = points[i]
+        if op == "pack":
+            (tp.pack if synchronous else tp.pack_async)(arena.data_ptr() + bases[i], 1, h, packed[i], p["packed_bytes"], 0, stream)
+        else:
+            (tp.unpack if synchronous else tp.unpack_async)(packed[i], p["packed_bytes"], 0, arena.data_ptr() + bases[i], 1, h, stream)
+        for key, _ in ovr:
+            tp.set_override(key, OVERRIDE_DEFAULTS[key])
+
     def run_step(events=None):
-        handles = []
-        for i, p in enumerate(points):
-            h = tp.type_from_recipe(p["recipe"])          # construct + commit
-            handles.append(h)
-            if not runs("pack", p):
-                continue
+        handles = {i: tp.type_from_recipe(points[i]["recipe"]) for i in used}   # construct + commit
+        for c, (op, i, ovr) in enumerate(calls):
             if events is not None:
-                events[0][i][0].record(stream)
-            tp.pack_async(arena.data_ptr() + bases[i], 1, h, packed[i], p["packed_bytes"], 0, stream)
+                events[c][0].record(stream)
+            one_call(op, i, ovr, handles[i])
             if events is not None:
-                events[0][i][1].record(stream)
-        for i, p in enumerate(points):
-            if not runs("unpack", p):
-                continue
-            if events is not None:
-                events[1][i][0].record(stream)
-            tp.unpack_async(packed[i], p["packed_bytes"], 0, arena.data_ptr() + bases[i], 1, handles[i], stream)
-            if events is not None:
-                events[1][i][1].record(stream)
+                events[c][1].record(stream)
         stream.synchronize()                               # completion
-        for h in handles:
+        for h in handles.values():
             if h >= 12:
                 tp.type_free(h)
 
     for _ in range(args.warmup):
         run_step()
-    plans = {"pack": [], "unpack": []}
-    for i, p in enumerate(points):
-        h = tp.type_from_recipe(p["recipe"])
-        plans["pack"].append("")
-        plans["unpack"].append("")
-        if only is None or runs("pack", p) or runs("unpack", p):
-            tp.pack(arena.data_ptr() + bases[i], 1, h, packed[i], p["packed_bytes"], 0, stream)
-            plans["pack"][i] = tp.last_plan().strip()
-            tp.unpack(packed[i], p["packed_bytes"], 0, arena.data_ptr() + bases[i], 1, h, stream)   # the bytes just packed
-            plans["unpack"][i] = tp.last_plan().strip()
+    handles = {i: tp.type_from_recipe(points[i]["recipe"]) for i in used}
+    if not args.points:
+        for i in used:   # every unpack restores the bytes its pack took
+            one_call("pack", i, (), handles[i], synchronous=True)
+    plans = []
+    for op, i, ovr in calls:
+        one_call(op, i, ovr, handles[i], synchronous=True)
+        plans.append(tp.last_plan().strip())
 
     def new_events():
-        return [[(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in points]
-                for _ in range(2)]
+        return [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls]
 
     all_events = [new_events() for _ in range(args.steps)]
     torch.cuda.synchronize()
@@ -222,39 +235,38 @@ def main(argv=None):
     t1 = time.perf_counter()
 
     step_s = (t1 - t0) / args.steps
-    ops = ("pack", "unpack")
-    bytes_per_step = sum(2 * p["packed_bytes"] for op in ops for p in points if runs(op, p))   # read + write
+    bytes_per_step = sum(2 * points[i]["packed_bytes"] for _, i, _ in calls)   # read + write
     value = bytes_per_step / step_s / 1e9
 
     # per-call device times from the HIP events recorded inside the timed region
     use_traffic = args.packed_bytes == PACKED_BYTES and not args.override
     kernels = []
-    for d, op in enumerate(ops):
-        for i, p in enumerate(points):
-            if not runs(op, p):
-                continue
-            ms = [all_events[k][d][i][0].elapsed_time(all_events[k][d][i][1]) for k in range(args.steps)]
-            avg_us = 1e3 * sum(ms) / len(ms)
-            srt = sorted(ms)
-            alg = 2 * p["packed_bytes"]
-            plan, nlaunch = summarise_plan(plans[op][i])
-            run = p["a"][0] if p["a"][0] < 512 else p["packed_bytes"]
-            k = {
-                "op": op, "a": list(p["a"]), "kernel": kernels_of(plans[op][i], op), "plan": plan,
-                "launches_per_call": nlaunch, "avg_us": round(avg_us, 2),
-                "median_us": round(1e3 * srt[len(srt) // 2], 2), "min_us": round(1e3 * srt[0], 2),
-                "algorithmic_bytes": alg, "gbs": round(alg / avg_us / 1e3, 1),
-                "frac_of_peak": round(alg / avg_us / 1e3 / HBM_PEAK_GBS, 4),
-                "sector_bound_frac_g128": round(sector_bound_fraction(run), 4),
-            }
-            m = MEASURED_TRAFFIC.get((op, p["a"][0]))
-            if m and use_traffic and m["plan"] == plan:   # HBM bytes actually moved, next to the algorithmic rate
-                k["hbm_traffic_fetch_write"] = [m["fetch"], m["write"]]
-                k["hbm_traffic_gbs"] = round((m["fetch"] + m["write"]) / avg_us / 1e3, 1)
-                k["hbm_traffic_frac_of_peak"] = round((m["fetch"] + m["write"]) / avg_us / 1e3 / HBM_PEAK_GBS, 4)
-            kernels.append(k)
+    for c, (op, i, ovr) in enumerate(calls):
+        p = points[i]
+        ms = [all_events[k][c][0].elapsed_time(all_events[k][c][1]) for k in range(args.steps)]
+        avg_us = 1e3 * sum(ms) / len(ms)
+        srt = sorted(ms)
+        alg = 2 * p["packed_bytes"]
+        plan, nlaunch = summarise_plan(plans[c])
+        run = p["a"][0] if p["a"][0] < 512 else p["packed_bytes"]
+        k = {
+            "op": op, "a": list(p["a"]), "kernel": kernels_of(plans[c], op), "plan": plan,
+            "launches_per_call": nlaunch, "avg_us": round(avg_us, 2),
+            "median_us": round(1e3 * srt[len(srt) // 2], 2), "min_us": round(1e3 * srt[0], 2),
+            "algorithmic_bytes": alg, "gbs": round(alg / avg_us / 1e3, 1),
+            "frac_of_peak": round(alg / avg_us / 1e3 / HBM_PEAK_GBS, 4),
+            "sector_bound_frac_g128": round(sector_bound_fraction(run), 4),
+        }
+        if ovr:
+            k["overrides"] = ["=".join(kv) for kv in ovr]
+        m = MEASURED_TRAFFIC.get((op, p["a"][0]))
+        if m and use_traffic and not ovr and m["plan"] == plan:   # HBM bytes actually moved, next to the algorithmic rate
+            k["hbm_traffic_fetch_write"] = [m["fetch"], m["write"]]
+            k["hbm_traffic_gbs"] = round((m["fetch"] + m["write"]) / avg_us / 1e3, 1)
+            k["hbm_traffic_frac_of_peak"] = round((m["fetch"] + m["write"]) / avg_us / 1e3 / HBM_PEAK_GBS, 4)
+        kernels.append(k)
     # the same-size plain copy through the same kernel (the dense a0 = 512 point) is the copy ceiling
-    ceiling = {k["op"]: k["gbs"] for k in kernels if k["a"][0] == 512}
+    ceiling = {k["op"]: k["gbs"] for k in kernels if k["a"][0] == 512 and "overrides" not in k}
     for k in kernels:
         if k["op"] in ceiling:
             k["frac_of_copy_ceiling"] = round(k["gbs"] / ceiling[k["op"]], 4)
@@ -287,7 +299,7 @@ def main(argv=None):
         "roofline": roofline,
         "kernels": kernels,
     }
-    if only is not None:
+    if args.points:
         out["config"]["only"] = args.points
 
     if not args.no_cpu_baseline:

@@ -100,12 +100,20 @@ int tp_type_create_subarray(int ndims, const int sizes[], const int subsizes[], 
  * the handle (word width, tile and grid follow at call time, when the addresses and the object
  * count are known).  Idempotent; host only; *t is not modified.
  * tp_type_free: drops the caller's reference and sets *t = TP_TYPE_NULL.  Predefined types
- * cannot be freed (TP_ERR_TYPE). */
+ * cannot be freed (TP_ERR_TYPE).  No passage of the paper: handle bookkeeping with the meaning of
+ * MPI_Type_free (a type built from *t keeps working). */
 int tp_type_commit(tp_type *t);
 int tp_type_free(tp_type *t);
 
-/* Size (data bytes of one object), lower bound and extent; pack size of `incount` objects
- * (= incount * size: the packed stream has no header). */
+/* tp_type_size: data bytes of one object (Sec. 2: the bytes the type map selects, the sum of its
+ *     block lengths).  tp_type_get_extent: lower bound and extent = ub - lb of the type map, the
+ *     distance between consecutive objects of a count (Sec. 2; the library keeps size, lb and ub per
+ *     node from construction, Sec. 3.1).  A subarray has lb 0 and the extent of its full array;
+ *     no alignment padding is added.
+ * tp_pack_size: bytes that `incount` objects occupy in the packed stream = incount * size (Sec. 6.2:
+ *     the packed buffer holds the selected bytes back to back, without a header).  TP_ERR_COUNT for a
+ *     negative count, TP_ERR_RANGE if the product overflows int64.
+ * All three work on any valid handle, committed or not; host only. */
 int tp_type_size(tp_type t, int64_t *size);
 int tp_type_get_extent(tp_type t, int64_t *lb, int64_t *extent);
 int tp_pack_size(int incount, tp_type t, int64_t *size);
@@ -136,6 +144,12 @@ int tp_pack_size(int incount, tp_type t, int64_t *size);
  * unpack of half a million or more tiny rows alternates read-only passes over its packed bytes with
  * the passes that store them), all on `hip_stream` and in order; none allocates or records a
  * memset, so a stream capture of the *_async forms replays from a HIP graph.
+ *
+ * Errors: every check (handle, count, fit, buffers, planning) comes before the first kernel is
+ * enqueued, and a call that fails one of them writes nothing and leaves *position unchanged.  The
+ * one error that can come later is TP_ERR_OTHER from the runtime refusing a launch or the final
+ * synchronize: *position is then unchanged as well, but launches of the same call that were
+ * enqueued before it may already have run, so the destination holds part of the data.
  */
 int tp_pack(const void *inbuf, int incount, tp_type t, void *outbuf, int64_t outsize, int64_t *position,
             void *hip_stream);
@@ -266,8 +280,8 @@ int tp_resource_stats(int kind, tp_resource_counts *out);
  *   "word"          "0" (automatic) or 1, 2, 4, 8, 16: upper limit on the access width in bytes
  *   "check_buffers" "1" (default) or "0": skip the per-call memory-residency queries (then the
  *                   buffers are taken to be GPU-addressable and large enough: the caller's duty)
- *   "nt"            "-1" (automatic), 0..3, 6 (unpack only) or 7: streaming hints, bit 0 = non-temporal
- *                   loads, bit 1 = non-temporal stores, bit 2 = the stores also written through L2 at once
+ *   "nt"            "-1" (automatic), 0..3, 6 or 7: streaming hints, bit 0 = non-temporal loads,
+ *                   bit 1 = non-temporal stores, bit 2 (with bit 1) = the stores also written through L2 at once
  *   "ur"            "-1" (automatic), 1 or 4: rows per thread where a run fits one workgroup
  *   "xpose"         "1" (default) or "0": allow the transposing kernel (tiles through LDS for
  *                   blocks whose short elements are adjacent along an outer dimension)
@@ -287,6 +301,9 @@ int tp_resource_stats(int kind, tp_resource_counts *out);
 int tp_type_get_strided_block(tp_type t, int *ndims, int64_t *start, int64_t counts[], int64_t strides[]);
 int tp_set_override(const char *key, const char *value);
 const char *tp_last_plan(void);
+/* tp_error_string: text for a TP_* code (for TP_ERR_OTHER the runtime's own message of the calling
+ * thread's last failure).  No passage of the paper: error reporting.  The string is owned by the
+ * library and valid until the thread's next failing call. */
 const char *tp_error_string(int code);
 
 #ifdef __cplusplus

@@ -39,34 +39,24 @@ def parse(text: str) -> dict:
     return table
 
 
-def _segment(axis, x):
-    """(index i, weight w): x sits at (1-w)*axis[i] + w*axis[i+1] on a log2 scale, clamped."""
-    if len(axis) == 1 or x <= axis[0]:
-        return 0, 0.0
-    if x >= axis[-1]:
-        return len(axis) - 2, 1.0
-    i = 0
-    while x > axis[i + 1]:
-        i += 1
-    return i, (math.log2(x) - math.log2(axis[i])) / (math.log2(axis[i + 1]) - math.log2(axis[i]))
-
-
 def query(table: dict, nbytes: float, block: float) -> dict:
-    """Interpolated seconds for each primitive."""
-    sizes, blocks = table["sizes"], table["blocks"]
-    scale = nbytes / sizes[-1] if nbytes > sizes[-1] else 1.0
-    si, sw = _segment(sizes, min(nbytes, sizes[-1]))
-    bi, bw = _segment(blocks, block)
-    s1, b1 = min(si + 1, len(sizes) - 1), min(bi + 1, len(blocks) - 1)
+    """Interpolated seconds for each primitive (Sec. 6.3: pack and unpack times come from a 2D
+    interpolation of sparse measurements, copy times from a 1D one).
+
+    Written as the definition: piecewise-linear interpolation of the measured times over log2 of the
+    axis values, first along the block-length axis for every measured size, then along the size axis.
+    numpy.interp holds its end values outside the measured range, which is the stated clamp; beyond
+    the largest measured size the time of that size grows in proportion to the bytes."""
+    log_sizes, log_blocks = np.log2(table["sizes"]), np.log2(table["blocks"])
+    top = float(table["sizes"][-1])
+    beyond = max(1.0, nbytes / top)
+    at_size, at_block = math.log2(min(nbytes, top)), math.log2(block)
     out = {}
     for name in PRIMITIVES[:4]:
-        g = table[name]
-        lo = (1 - bw) * g[si, bi] + bw * g[si, b1]
-        hi = (1 - bw) * g[s1, bi] + bw * g[s1, b1]
-        out[name] = ((1 - sw) * lo + sw * hi) * scale
+        per_size = [np.interp(at_block, log_blocks, row) for row in table[name]]
+        out[name] = float(np.interp(at_size, log_sizes, per_size)) * beyond
     for name in PRIMITIVES[4:]:
-        v = table[name]
-        out[name] = ((1 - sw) * v[si] + sw * v[s1]) * scale
+        out[name] = float(np.interp(at_size, log_sizes, table[name])) * beyond
     return out
 
 

@@ -149,6 +149,9 @@ def byte_displacements(t, incount: int = 1):
 
 
 def has_overlap(t, incount: int = 1) -> bool:
+    """True if some byte is selected more than once by `incount` objects of `t` (MPI-3.1 Sec. 4.1:
+    such a type may be sent from but not received into; the tests use this to decide whether an
+    unpack has a unique result).  Pinned in tests/test_oracle_pins.py by hand-worked cases."""
     b = byte_displacements(t, incount)
     return len(set(b)) != len(b)
 

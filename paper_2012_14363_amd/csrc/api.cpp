@@ -472,7 +472,7 @@ int tp_set_override(const char* key, const char* value) {
         return kSuccess;
     }
     if (!std::strcmp(key, "nt")) {
-        if ((v < -1 || v > 3) && v != 7) return kErrArg;
+        if ((v < -1 || v > 3) && v != 6 && v != 7) return kErrArg;
         g_nt.store(static_cast<int>(v));
         return kSuccess;
     }

@@ -150,9 +150,7 @@ struct PickKernel {
         case 1: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 1>; break;
         case 2: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 2>; break;
         case 3: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 3>; break;
-        case 6:
-            if constexpr (UNPACK) fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 6>;
-            break;
+        case 6: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 6>; break;
         case 7: fn = tile_kernel<WLOG2, UX, UR, UNPACK, NRD, 7>; break;
         default: break;
         }
@@ -162,7 +160,7 @@ struct PickKernel {
 }  // namespace
 
 hipError_t enqueue(const Launch& l, bool unpack, hipStream_t stream) {
-    if (l.nblocks == 0 || l.grid > l.nblocks) return hipErrorInvalidValue;
+    if (l.nblocks == 0 || l.grid > l.nblocks || (l.grid ? l.grid : l.nblocks) > kMaxGrid) return hipErrorInvalidValue;
     const dim3 grid(l.grid ? l.grid : l.nblocks), block(kBlockThreads);
     if (l.kind == kXpose) {
         if (l.grid) return hipErrorInvalidValue;
@@ -194,7 +192,7 @@ hipError_t enqueue(const Launch& l, bool unpack, hipStream_t stream) {
 }
 
 hipError_t enqueue_batch(const BatchParams& b, bool unpack, hipStream_t stream) {
-    if (b.n == 0 || b.nblocks == 0) return hipErrorInvalidValue;
+    if (b.n == 0 || b.nblocks == 0 || b.nblocks > kMaxGrid) return hipErrorInvalidValue;
     if (unpack) hipLaunchKernelGGL(batch_kernel<true>, dim3(b.nblocks), dim3(kBlockThreads), 0, stream, b);
     else hipLaunchKernelGGL(batch_kernel<false>, dim3(b.nblocks), dim3(kBlockThreads), 0, stream, b);
     return hipGetLastError();

@@ -98,6 +98,7 @@ struct Splitter {
         const uint64_t nrc = (rows + uint64_t{br} * l.ur - 1) / (uint64_t{br} * l.ur);
         l.nblocks = static_cast<uint32_t>(nrc * p.nxc);
         if (grid) l.grid = std::min(grid, l.nblocks);
+        else if (l.nblocks > kMaxGrid) l.grid = kMaxGrid;   // more tiles than a grid may have workgroups
         out->push_back(l);
     }
 
@@ -251,11 +252,11 @@ bool plan_xpose(const PlanInput& in, const std::vector<Dim>& dims, const char* t
             x.opstride[x.nod] = pstride;
             ++x.nod;
             blocks *= static_cast<uint64_t>(dims[d].count);
-            if (blocks >= (uint64_t{1} << 30)) return false;
+            if (blocks > kMaxGrid) return false;
         }
         pstride *= dims[d].count;
     }
-    if (blocks >= (uint64_t{1} << 30)) return false;
+    if (blocks > kMaxGrid) return false;   // one tile per workgroup
     l.nblocks = static_cast<uint32_t>(blocks);
     out->push_back(l);
     return true;
@@ -497,8 +498,8 @@ void make_batches(const std::vector<Launch>& launches, std::vector<BatchParams>*
             singles->push_back(l);
             continue;
         }
-        // block ids stay below 2^31 so the in-kernel multiply-shift division holds
-        if (group.size() == static_cast<size_t>(kBatchMax) || group_blocks + l.nblocks >= (uint64_t{1} << 31)) flush();
+        // one tile per workgroup: a batch has at most as many tiles as a grid may have workgroups
+        if (group.size() == static_cast<size_t>(kBatchMax) || group_blocks + l.nblocks > kMaxGrid) flush();
         group.push_back(&l);
         group_blocks += l.nblocks;
     }

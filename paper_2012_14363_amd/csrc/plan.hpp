@@ -13,6 +13,10 @@
 namespace tp {
 
 constexpr int kBlockThreads = 256;  // four wave64 per workgroup
+// The runtime launches no grid of 2^32 threads or more: with 256-thread workgroups a launch has at
+// most 2^24 - 1 of them.  Launches of more tiles run on that many workgroups, each taking every
+// gridDim.x-th tile; launches whose kernels take one tile per workgroup stay below it.
+constexpr uint32_t kMaxGrid = (1u << 24) - 1;
 
 // Everything one kernel launch needs; passed by value in the kernel-argument
 // segment, so no datatype metadata ever lives in device memory.

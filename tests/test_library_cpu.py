@@ -284,6 +284,7 @@ def _emulate_roundtrip(t, incount, *, typed_shift=0, packed_shift=0, position=0,
         assert np.array_equal(dst, want), (t, back["plan"])
         res["unpack_plan"] = back["plan"]
         res["unpack_prefetched_span"] = back["prefetched_span"]
+        res["unpack_compared"] = True
     if h >= 12:
         tp.type_free(h)
     return res
@@ -291,10 +292,14 @@ def _emulate_roundtrip(t, incount, *, typed_shift=0, packed_shift=0, position=0,
 
 def test_emulated_kernels_match_oracle_on_random_types():
     rng = random.Random(303)
+    compared = 0
     for i, t in enumerate(_random_types(301, 250, allow_negative=True, allow_zero=False)):
-        _emulate_roundtrip(t, rng.randint(1, 3), typed_shift=rng.choice((0, 0, 1, 2, 4, 8)),
-                           packed_shift=rng.choice((0, 0, 1, 2, 4, 8)), position=rng.choice((0, 3, 16)),
-                           stage=rng.choice((-1, 1)), stage_bytes=rng.choice((0, 4096)))
+        res = _emulate_roundtrip(t, rng.randint(1, 3), typed_shift=rng.choice((0, 0, 1, 2, 4, 8)),
+                                 packed_shift=rng.choice((0, 0, 1, 2, 4, 8)), position=rng.choice((0, 3, 16)),
+                                 stage=rng.choice((-1, 1)), stage_bytes=rng.choice((0, 4096)))
+        compared += bool(res.get("unpack_compared"))
+    # types whose map overlaps itself have no unique unpack and are only packed: they must stay the exception
+    assert compared >= 200, compared
 
 
 @pytest.mark.parametrize("a0", [1, 2, 4, 8, 16, 48, 64, 200, 512, 1040, 4100, 4112])
@@ -574,11 +579,14 @@ def test_emulated_batch_of_different_types():
         assert res["rewritten"] == 0
     want = np.full(typed_len, 0xA5, dtype=np.uint8)
     pos = 3
+    compared = 0
     for t, count, origin in recipes:
         if not py.has_overlap(t, count):
             pos = cc.unpack(expect, pos, want, origin, count, t)
+            compared += 1
         else:
             pos += py.size(t) * count
+    assert compared >= 60, compared   # overlapping maps (no unique unpack) stay the exception
     ok = np.ones(typed_len, dtype=bool)
     for t, count, origin in recipes:
         if py.has_overlap(t, count):

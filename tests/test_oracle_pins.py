@@ -330,3 +330,51 @@ def test_truncation_and_bounds_are_errors():
             o.pack(src, 0, 1, t, np.zeros(5, np.uint8), 0)
         with pytest.raises(IndexError):
             o.pack(src[:9], 0, 1, t, np.zeros(6, np.uint8), 0)
+
+
+# --------------------------------------------------------------- has_overlap
+def test_has_overlap_on_hand_worked_cases():
+    """`has_overlap` decides whether a test may compare an unpack at all, so it is pinned in both
+    directions by cases worked out by hand (none of them computed with the oracle)."""
+    # two blocks of two bytes one byte apart: bytes 0 1 | 1 2
+    assert py.has_overlap(vector(2, 2, 1, BYTE))
+    # a stride of zero puts both copies on the same byte
+    assert py.has_overlap(hvector(2, 1, 0, BYTE))
+    # 4-byte elements placed 2 bytes apart
+    assert py.has_overlap(hvector(3, 1, 2, FLOAT))
+    # a negative stride that walks back over the first block: bytes 0..3 then -2..1
+    assert py.has_overlap(hvector(2, 1, -2, contiguous(4, BYTE)))
+    # the nested workload: rows 16384 apart inside planes 8192 apart, (j, i) = (1, 0) and (0, 2) collide
+    assert py.has_overlap(W.configs.cfg5()["recipe"])
+    # disjoint: blocks that touch but do not cross, gaps, negative strides that clear the block
+    assert not py.has_overlap(vector(3, 2, 4, BYTE))
+    assert not py.has_overlap(vector(2, 2, 2, BYTE))            # bytes 0 1 | 2 3: adjacent
+    assert not py.has_overlap(hvector(2, 1, -4, contiguous(4, BYTE)))
+    assert not py.has_overlap(contiguous(2, vector(2, 1, 2, BYTE)))   # extent 3: bytes 0 2 | 3 5
+    assert not py.has_overlap(W.configs.cfg1()["recipes"]["vector"])
+    assert not py.has_overlap(W.configs.cfg2_point(4, 1 << 12)["recipe"])
+    assert not py.has_overlap(subarray((4, 6), (2, 3), (1, 2), "C", BYTE))
+    # several objects sit one extent apart, and the extent spans every copy: objects of a disjoint
+    # type never collide, objects of a colliding type still do
+    assert not py.has_overlap(vector(3, 2, 4, BYTE), 3)
+    assert not py.has_overlap(hvector(2, 1, -4, contiguous(4, BYTE)), 2)
+    assert py.has_overlap(vector(2, 2, 1, BYTE), 2)
+
+
+def test_has_overlap_equals_a_byte_census_on_random_trees():
+    # brute force, another way round: mark every selected byte in an array and look for a second mark
+    both = {True: 0, False: 0}
+    for t in _random_types(909, 400, allow_negative=True):
+        incount = 2
+        blocks = [b for obj in range(incount) for b in py.type_map(t, obj * py.extent(t))]
+        if not blocks:
+            assert not py.has_overlap(t, incount)
+            continue
+        lo = min(d for d, _ in blocks)
+        marks = np.zeros(max(d + n for d, n in blocks) - lo, dtype=np.int32)
+        for d, n in blocks:
+            marks[d - lo:d - lo + n] += 1
+        expect = bool((marks > 1).any())
+        assert py.has_overlap(t, incount) == expect, t
+        both[expect] += 1
+    assert both[True] >= 20 and both[False] >= 100, both
