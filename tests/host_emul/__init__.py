@@ -38,6 +38,8 @@ def _load():
         L.emul_transfer_batch.argtypes = [ctypes.c_int, ctypes.c_int, pint, p64, p64, p64, p64, p64, p64, p64, vp, i64,
                                           vp, i64, i64, vp, p64]
         L.emul_transfer_batch.restype = ctypes.c_int
+        L.emul_plan_only.argtypes = [ctypes.c_int, ctypes.c_int, i64, p64, p64, i64, i64, i64, i64, ctypes.c_int, p64, i64]
+        L.emul_plan_only.restype = i64
         L.emul_fastdiv_mismatches.argtypes = [ctypes.c_uint32, i64, ctypes.c_uint64]
         L.emul_fastdiv_mismatches.restype = i64
         L.cache_emul_new.restype = vp
@@ -163,6 +165,23 @@ def transfer(unpack, block, extent, count, typed, origin, packed, position, *, m
     return {"rc": rc, "oob": result[0], "unaligned": result[1], "rewritten": result[2], "launches": result[3],
             "duplicates": result[4], "prefetched_span": result[5], "misplaced": result[6], "plan": text.value.decode(),
             "write_count": wc}
+
+
+def plan_only(unpack, block, extent, count, typed_address=1 << 40, packed_address=1 << 44, batched=False):
+    """Plans tp_pack / tp_unpack of a block at made-up addresses without touching memory.  Returns the
+    launches as dicts (tiles, grid = workgroups asked for, rows, kind: 0 tile, 1 transposing, 2 read-only
+    pass, 100 batched)."""
+    start, counts, strides = block
+    nd = len(counts)
+    arr = ctypes.c_int64 * nd
+    cap = 1 << 16
+    out = (ctypes.c_int64 * (4 * cap))()
+    n = _load().emul_plan_only(int(unpack), nd, start, arr(*counts), arr(*strides), extent, count, typed_address,
+                               packed_address, int(batched), out, cap)
+    if n < 0:
+        raise ValueError(f"planner status {-n}")
+    assert n <= cap
+    return [dict(zip(("tiles", "grid", "rows", "kind"), out[4 * i:4 * i + 4])) for i in range(n)]
 
 
 def transfer_batch(unpack, requests, typed, packed, position, count_writes=True):

@@ -225,6 +225,49 @@ int emul_transfer(int unpack, int ndims, int64_t start, const int64_t* counts, c
     return 0;
 }
 
+// Plans a transfer without running it (no buffer is touched, so the shapes may be far larger than
+// host memory): per launch, launches[4*i..] = tiles, workgroups the launch asks for, rows, kind.
+// Returns the number of launches (filling at most `cap` of them), or minus a TP_* status.
+int64_t emul_plan_only(int unpack, int ndims, int64_t start, const int64_t* counts, const int64_t* strides, int64_t extent,
+                       int64_t count, int64_t typed_address, int64_t packed_address, int batched, int64_t* launches,
+                       int64_t cap) {
+    tp::PlanInput in;
+    in.block.ndims = ndims;
+    in.block.start = start;
+    for (int d = 0; d < ndims; ++d) {
+        in.block.counts[d] = counts[d];
+        in.block.strides[d] = strides[d];
+    }
+    in.extent = extent;
+    in.count = count;
+    in.typed = reinterpret_cast<const char*>(static_cast<intptr_t>(typed_address));
+    in.packed = reinterpret_cast<char*>(static_cast<intptr_t>(packed_address));
+    in.unpack = unpack != 0;
+    in.batched = batched != 0;
+    std::vector<tp::Launch> planned;
+    const int rc = tp::plan_launches(in, &planned);
+    if (rc != tp::kSuccess) return -rc;
+    std::vector<tp::Launch> singles = planned;
+    std::vector<tp::BatchParams> batches;
+    if (batched) {
+        singles.clear();
+        tp::make_batches(planned, &batches, &singles);
+    }
+    int64_t n = 0;
+    auto put = [&](int64_t tiles, int64_t grid, int64_t rows, int64_t kind) {
+        if (n < cap) {
+            launches[4 * n] = tiles;
+            launches[4 * n + 1] = grid;
+            launches[4 * n + 2] = rows;
+            launches[4 * n + 3] = kind;
+        }
+        ++n;
+    };
+    for (const tp::BatchParams& b : batches) put(b.nblocks, b.nblocks, 0, 100);
+    for (const tp::Launch& l : singles) put(l.nblocks, l.grid ? l.grid : l.nblocks, l.kind == tp::kTile ? l.p.nrows : 0, l.kind);
+    return n;
+}
+
 // Multiply-shift division (fastdiv.hpp) against the hardware divide: every divisor in
 // [1, small_limit] with dividends around multiples of it and at the range ends, plus `random_pairs`
 // pseudo-random (dividend < 2^31, divisor) pairs, powers of two included.  Returns the mismatches.
