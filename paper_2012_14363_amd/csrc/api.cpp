@@ -56,25 +56,12 @@ int register_type(TypePtr node, tp_type* newtype) {
     return kSuccess;
 }
 
-// Commit = Sec. 3's three phases, run once per node and cached in it.
-int commit_node(const TypeNode& node) {
-    std::call_once(node.commit_once, [&node] {
-        StridedBlock sb;
-        const int rc = canonicalize(node, &sb);
-        node.commit_status = rc;
-        if (rc != kSuccess) return;
-        node.block = sb;
-        node.committed.store(true, std::memory_order_release);
-    });
-    return node.commit_status;
-}
-
 // A handle's node if it may be used for data movement: committed, or predefined
 // (predefined types count as committed from the start and are committed on first use).
 TypePtr committed_node(tp_type t) {
     TypePtr node = HandleTable::instance().lookup(t);
     if (!node) return nullptr;
-    if (node->kind == Kind::Named && commit_node(*node) != kSuccess) return nullptr;
+    if (node->kind == Kind::Named && commit(*node) != kSuccess) return nullptr;
     return node->committed.load(std::memory_order_acquire) ? node : nullptr;
 }
 
@@ -360,7 +347,7 @@ int tp_type_commit(tp_type* t) {
     if (!t) return kErrArg;
     const TypePtr node = HandleTable::instance().lookup(*t);
     if (!node) return kErrType;
-    return commit_node(*node);
+    return commit(*node);
 }
 
 int tp_type_free(tp_type* t) {

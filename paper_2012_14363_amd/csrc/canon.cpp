@@ -178,4 +178,16 @@ int canonicalize(const TypeNode& type, StridedBlock* out) {
     return strided_block(chain, out);
 }
 
+int commit(const TypeNode& node) {
+    std::call_once(node.commit_once, [&node] {
+        StridedBlock sb;
+        const int rc = canonicalize(node, &sb);
+        node.commit_status = rc;
+        if (rc != kSuccess) return;
+        node.block = sb;
+        node.committed.store(true, std::memory_order_release);
+    });
+    return node.commit_status;
+}
+
 }  // namespace tp

@@ -41,4 +41,8 @@ int strided_block(const Chain& chain, StridedBlock* out);
 // translate + simplify + strided_block; an empty type gives ndims 1, counts[0] 0.
 int canonicalize(const TypeNode& type, StridedBlock* out);
 
+// Commit: the three phases above, run once per node whichever threads ask, and cached in it
+// (Sec. 3: the result is kept with the datatype).  Returns the node's commit status.
+int commit(const TypeNode& node);
+
 }  // namespace tp
