@@ -228,6 +228,25 @@ int tp_pack_host(const void *inbuf, int incount, tp_type t, void *host_outbuf, i
 int tp_unpack_host(const void *host_inbuf, int64_t insize, int64_t *position, void *outbuf, int outcount, tp_type t,
                    void *staging, int64_t staging_size, int method, void *hip_stream, int *method_used);
 
+/* tp_pack_host_static: for callers that cannot allocate - tight serving loops, harnesses that
+ * forbid hipMalloc, code that runs while another thread captures a HIP graph (it synchronizes its
+ * stream, so it is not itself for use on a capturing stream).  It is tp_pack_host with TP_METHOD_STAGED
+ * whose staging buffer is neither the caller's nor leased: a fixed array of
+ * TP_STATIC_STAGING_BYTES that is part of the library's device image (each GPU the library runs on
+ * holds its own copy until the process ends).  The call gathers the objects into that array with
+ * the pack kernels, copies exactly incount*size bytes from it to host_outbuf + *position with a
+ * dense copy kernel, synchronizes the stream and advances *position.  It calls no hipMalloc,
+ * hipFree or other allocating routine; inbuf must be device memory and host_outbuf pinned,
+ * GPU-mapped host memory (or device memory), both checked as in tp_pack.
+ * Errors: as tp_pack, plus TP_ERR_RANGE if incount*size exceeds TP_STATIC_STAGING_BYTES (nothing
+ * is written; use tp_pack_host with a staging buffer of your own for larger messages).
+ * All calls on one GPU share that GPU's array, which keeps the last call's bytes: the call itself
+ * needs nothing cleared (it reads back only what it has just written), but two calls that overlap
+ * in time on one GPU - from two threads, or on two streams - race on it.  Serialize them. */
+#define TP_STATIC_STAGING_BYTES (4 << 20)
+int tp_pack_host_static(const void *inbuf, int incount, tp_type t, void *host_outbuf, int64_t outsize,
+                        int64_t *position, void *hip_stream);
+
 /* ---- resource cache (Sec. 5) ------------------------------------------------------------------
  * A send/receive layer built on this library needs, per message, an intermediate buffer (device
  * or pinned host), often a stream and an event.  Creating them costs the runtime microseconds to

@@ -32,7 +32,7 @@ EXPORTS = (
     "tp_pack", "tp_unpack", "tp_pack_async", "tp_unpack_async",
     "tp_pack_batch", "tp_unpack_batch", "tp_pack_batch_async", "tp_unpack_batch_async",
     "tp_model_measure", "tp_model_save", "tp_model_load", "tp_model_query", "tp_model_select",
-    "tp_pack_host", "tp_unpack_host",
+    "tp_pack_host", "tp_unpack_host", "tp_pack_host_static",
     "tp_resource_acquire", "tp_resource_release", "tp_resource_trim", "tp_resource_stats",
     "tp_type_get_strided_block", "tp_set_override", "tp_last_plan", "tp_error_string",
 )
@@ -111,6 +111,7 @@ def lib() -> ctypes.CDLL:
             "tp_model_select": [i32, ctypes.c_int, ctypes.c_double, ctypes.c_double, pint,
                                 ctypes.POINTER(ctypes.c_double)],
             "tp_pack_host": [vp, ctypes.c_int, i32, vp, i64, pi64, vp, i64, ctypes.c_int, vp, pint],
+            "tp_pack_host_static": [vp, ctypes.c_int, i32, vp, i64, pi64, vp],
             "tp_unpack_host": [vp, i64, pi64, vp, ctypes.c_int, i32, vp, i64, ctypes.c_int, vp, pint],
             "tp_resource_acquire": [ctypes.c_int, i64, pvp],
             "tp_resource_release": [ctypes.c_int, vp],
@@ -345,6 +346,17 @@ def pack_host(inbuf, incount, t, host_outbuf, outsize, position, staging=None, s
                             ctypes.byref(used))
     _check(rc, "tp_pack_host")
     return pos.value, used.value
+
+
+TP_STATIC_STAGING_BYTES = 4 << 20
+
+
+def pack_host_static(inbuf, incount, t, host_outbuf, outsize, position, stream=None) -> int:
+    """tp_pack_host_static (staged through the library's fixed device array; allocates nothing); returns the new position."""
+    pos = ctypes.c_int64(position)
+    rc = lib().tp_pack_host_static(_ptr(inbuf), incount, t, _ptr(host_outbuf), outsize, ctypes.byref(pos), _stream(stream))
+    _check(rc, "tp_pack_host_static")
+    return pos.value
 
 
 def unpack_host(host_inbuf, insize, position, outbuf, outcount, t, staging=None, staging_size=0,

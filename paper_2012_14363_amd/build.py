@@ -10,7 +10,7 @@ CSRC = os.path.join(PKG_DIR, "csrc")
 INCLUDE = os.path.join(os.path.dirname(PKG_DIR), "include")
 LIB_PATH = os.path.join(PKG_DIR, "libtp_pack.so")
 
-SOURCES = ["api.cpp", "model_api.cpp", "model.cpp", "resource_api.cpp", "resource_cache.cpp", "type_tree.cpp",
+SOURCES = ["api.cpp", "static_staging.cpp", "model_api.cpp", "model.cpp", "resource_api.cpp", "resource_cache.cpp", "type_tree.cpp",
            "canon.cpp", "plan.cpp", "kernels.hip"]
 
 

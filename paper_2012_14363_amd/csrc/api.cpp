@@ -17,6 +17,7 @@
 #include "plan.hpp"
 #include "resource_cache.hpp"
 #include "status.hpp"
+#include "transfer.hpp"
 #include "type_tree.hpp"
 
 namespace {
@@ -211,11 +212,13 @@ int finish(hipStream_t stream, bool synchronize) {
 }
 
 int transfer(bool unpack, const void* typed_buf, int64_t count, tp_type t, const void* packed_buf,
-             int64_t packed_size, int64_t* position, void* hip_stream, bool synchronize) {
+             int64_t packed_size, int64_t* position, void* hip_stream, bool synchronize,
+             const MemRange* vouched = nullptr) {
     if (!position) return kErrArg;
     if (*position < 0 || packed_size < 0) return kErrArg;
     t_last_plan.clear();
     BufferMap memory(buffer_query());
+    if (vouched) memory.add_known(*vouched);
     TypePtr node;
     int64_t bytes = 0;
     int rc = check_request(typed_buf, count, t, packed_buf, packed_size, *position, &node, &bytes);
@@ -299,6 +302,55 @@ int transfer_batch(bool unpack, int n, const void* const* typed_bufs, const int*
 }
 
 }  // namespace
+
+namespace tp {
+
+int transfer_with_device_buffer(bool unpack, const void* typed_buf, int64_t count, tp_type t, void* device_buf,
+                                int64_t size, int64_t* position, hipStream_t stream) {
+    if (!device_buf || size < 0) return kErrArg;
+    MemRange mine;
+    mine.lo = reinterpret_cast<uintptr_t>(device_buf);
+    mine.hi = mine.lo + static_cast<uintptr_t>(size);
+    return transfer(unpack, typed_buf, count, t, device_buf, size, position, stream, false, &mine);
+}
+
+int copy_device_buffer_to_packed(const void* device_src, int64_t bytes, void* packed_buf, int64_t packed_size,
+                                 int64_t position, hipStream_t stream) {
+    if (bytes < 0 || position < 0 || packed_size < 0) return kErrArg;
+    if (bytes > packed_size - position) return kErrTruncate;
+    if (bytes == 0) return kSuccess;
+    if (!device_src || !packed_buf) return kErrBuffer;
+    BufferMap memory(buffer_query());
+    const char* first = static_cast<const char*>(packed_buf) + position;
+    const char* view = nullptr;
+    bool on_host = false;
+    int rc = memory.locate(first, true, &view, &on_host);
+    if (rc != kSuccess) return rc;
+    if ((rc = memory.check(first + bytes - 1, true)) != kSuccess) return rc;
+    PlanInput in;   // one run of `bytes`: the fully dense datatype
+    in.block.ndims = 1;
+    in.block.start = 0;
+    in.block.counts[0] = bytes;
+    in.block.strides[0] = 1;
+    in.extent = bytes;
+    in.count = 1;
+    in.typed = static_cast<const char*>(device_src);
+    in.packed = const_cast<char*>(view);
+    in.packed_on_host = on_host;
+    std::vector<Launch> launches;
+    rc = plan_launches(in, &launches);
+    if (rc != kSuccess) return rc;
+    for (const Launch& l : launches) {
+        const hipError_t e = enqueue(l, false, stream);
+        if (e != hipSuccess) {
+            t_last_hip_error = hipGetErrorString(e);
+            return kErrOther;
+        }
+    }
+    return kSuccess;
+}
+
+}  // namespace tp
 
 extern "C" {
 

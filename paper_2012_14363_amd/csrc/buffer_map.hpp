@@ -63,6 +63,9 @@ public:
         return locate(p, allow_host, &ignored);
     }
 
+    // Memory the library itself vouches for (its own buffers): addresses inside need no query.
+    void add_known(const MemRange& range) { known_.push_back(range); }
+
     size_t known_ranges() const { return known_.size(); }
 
 private:
