@@ -15,7 +15,12 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "typemap_oracle.c")
-_LIB = os.path.join(_HERE, "libtypemap_oracle.so")
+# TP_SANITIZE=address / thread: an instrumented build under a name of its own (for the CPU tests only;
+# the loading process needs the sanitizer's runtime preloaded)
+_SANITIZE = os.environ.get("TP_SANITIZE", "")
+_SANITIZE_FLAGS = {"": [], "address": ["-fsanitize=address,undefined", "-fno-omit-frame-pointer"],
+                   "thread": ["-fsanitize=thread", "-fno-omit-frame-pointer"]}[_SANITIZE]
+_LIB = os.path.join(_HERE, f"libtypemap_oracle{'.' + _SANITIZE if _SANITIZE else ''}.so")
 
 _NAMED_SIZE = {
     "BYTE": 1, "CHAR": 1, "INT8": 1, "UINT8": 1, "INT16": 2, "UINT16": 2,
@@ -30,7 +35,8 @@ def build(force: bool = True) -> str:
     """Compile the C oracle with gcc (a checker, not part of the product)."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         subprocess.check_call(
-            ["gcc", "-O2", "-g", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared", "-pthread", _SRC, "-o", _LIB]
+            ["gcc", "-O2", "-g", "-std=c11", "-Wall", "-Wextra", "-fPIC", "-shared", "-pthread", *_SANITIZE_FLAGS, _SRC,
+             "-o", _LIB]
         )
     return _LIB
 

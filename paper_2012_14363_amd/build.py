@@ -38,8 +38,6 @@ def build(verbose: bool = False) -> str:
     subprocess.check_call(cmd)
     for tool in C_TOOLS:
         build_c_tool(tool)
-    for tool in HIP_TOOLS:
-        build_hip_tool(tool)
     return LIB_PATH
 
 
@@ -56,22 +54,6 @@ def build_c_tool(name: str) -> str:
     subprocess.check_call([
         "gcc", "-O2", "-std=c11", "-Wall", "-Wextra", "-I", INCLUDE, os.path.join(CSRC, name + ".c"),
         "-L", PKG_DIR, "-ltp_pack", "-Wl,-rpath,$ORIGIN", "-Wl,-rpath-link," + "/opt/rocm/lib", "-o", exe,
-    ])
-    return exe
-
-
-# stand-alone HIP programs (measurements that stand beside the library, not part of it)
-HIP_TOOLS = ("partial_line_probe",)
-PROBE_EXE = os.path.join(PKG_DIR, "partial_line_probe")
-
-
-def build_hip_tool(name: str) -> str:
-    """Compiles csrc/<name>.hip for gfx950 into an executable of its own."""
-    exe = os.path.join(PKG_DIR, name)
-    subprocess.check_call([
-        hipcc(), "-O3", "-std=c++17", "--offload-arch=gfx950",
-        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
-        os.path.join(CSRC, name + ".hip"), "-o", exe,
     ])
     return exe
 

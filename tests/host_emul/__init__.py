@@ -10,18 +10,26 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(os.path.dirname(_HERE))
 _CSRC = os.path.join(_ROOT, "paper_2012_14363_amd", "csrc")
-_LIB = os.path.join(_HERE, "libtp_emul.so")
-_SOURCES = [os.path.join(_HERE, "emul.cpp"), os.path.join(_HERE, "cache_emul.cpp"), os.path.join(_CSRC, "plan.cpp"),
-            os.path.join(_CSRC, "resource_cache.cpp")]
+# TP_SANITIZE=address (AddressSanitizer + UndefinedBehaviorSanitizer) or =thread (ThreadSanitizer) builds
+# this library, and the C oracle, instrumented and under a name of its own; the process that loads it
+# must have the sanitizer's runtime preloaded (README: "Sanitizer builds").  CPU only.
+SANITIZE = os.environ.get("TP_SANITIZE", "")
+SANITIZE_FLAGS = {"": [], "address": ["-fsanitize=address,undefined", "-fno-omit-frame-pointer"],
+                  "thread": ["-fsanitize=thread", "-fno-omit-frame-pointer"]}[SANITIZE]
+_LIB = os.path.join(_HERE, f"libtp_emul{'.' + SANITIZE if SANITIZE else ''}.so")
+_SOURCES = [os.path.join(_HERE, "emul.cpp"), os.path.join(_HERE, "cache_emul.cpp"), os.path.join(_HERE, "types_emul.cpp"),
+            os.path.join(_CSRC, "plan.cpp"), os.path.join(_CSRC, "resource_cache.cpp"), os.path.join(_CSRC, "type_tree.cpp"),
+            os.path.join(_CSRC, "canon.cpp")]
 _lib = None
 
 
 def build(force=True):
-    deps = _SOURCES + [os.path.join(_CSRC, h) for h in ("plan.hpp", "tile_body.hpp", "fastdiv.hpp", "strided_block.hpp", "resource_cache.hpp", "buffer_map.hpp")]
+    deps = _SOURCES + [os.path.join(_CSRC, h) for h in ("plan.hpp", "tile_body.hpp", "fastdiv.hpp", "strided_block.hpp",
+                                                         "resource_cache.hpp", "buffer_map.hpp", "type_tree.hpp", "canon.hpp")]
     stale = not os.path.exists(_LIB) or any(os.path.getmtime(d) > os.path.getmtime(_LIB) for d in deps)
     if force or stale:
         subprocess.check_call(["g++", "-O2", "-g", "-std=c++20", "-Wall", "-Wextra", "-Wno-unknown-pragmas", "-fPIC",
-                               "-shared", "-pthread", "-I", _CSRC, *_SOURCES, "-o", _LIB])
+                               "-shared", "-pthread", *SANITIZE_FLAGS, "-I", _CSRC, *_SOURCES, "-o", _LIB])
     return _LIB
 
 
@@ -40,6 +48,8 @@ def _load():
         L.emul_transfer_batch.restype = ctypes.c_int
         L.emul_plan_only.argtypes = [ctypes.c_int, ctypes.c_int, i64, p64, p64, i64, i64, i64, i64, ctypes.c_int, p64, i64]
         L.emul_plan_only.restype = i64
+        L.types_emul_hammer.argtypes = [ctypes.c_int, ctypes.c_int]
+        L.types_emul_hammer.restype = i64
         L.emul_fastdiv_mismatches.argtypes = [ctypes.c_uint32, i64, ctypes.c_uint64]
         L.emul_fastdiv_mismatches.restype = i64
         L.cache_emul_new.restype = vp
@@ -137,6 +147,12 @@ def cache_fail_next(n):
 
 def cache_set_device(d):
     _load().cache_emul_set_device(d)
+
+
+def types_hammer(threads, rounds):
+    """Threads building, committing, looking up and freeing datatypes through the library's handle table
+    (types_emul.cpp); returns the number of wrong results."""
+    return _load().types_emul_hammer(threads, rounds)
 
 
 def fastdiv_mismatches(small_limit, random_pairs, seed):

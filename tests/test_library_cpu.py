@@ -675,6 +675,12 @@ def test_multiply_shift_division_is_exact():
     assert host_emul.fastdiv_mismatches(100000, 3000000, 12345) == 0
 
 
+def test_handle_table_hammered_by_threads_in_the_host_build():
+    # the library's type tree, handle table and commit, compiled for the host (tests/host_emul/types_emul.cpp):
+    # eight threads build, commit, look up and free types at once, one node committed by all of them
+    assert host_emul.types_hammer(8, 3000) == 0
+
+
 def test_handle_table_and_commit_are_thread_safe():
     import threading
 
