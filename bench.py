@@ -78,6 +78,46 @@ def sector_bound_fraction(run: int, granule: int = 128) -> float:
 # Keyed by (op, a0): the plan the call had when the counters were read (tp_last_plan, summarised), bytes
 # fetched, bytes written.  A point whose plan differs today reports no traffic rather than a stale one.
 MEASURED_TRAFFIC = {
+    ('pack', 1): {"plan": 'tile W=1 ux=1 ur=4 nt=3 bx=1 n0=1 back=0 rows=67108864 nrd=1 blocks=65536',
+                   "fetch": 8585919339, "write": 72456804},
+    ('pack', 2): {"plan": 'tile W=1 ux=1 ur=4 nt=3 bx=2 n0=2 back=0 rows=33554432 nrd=1 blocks=65536',
+                   "fetch": 4293031572, "write": 72045842},
+    ('pack', 4): {"plan": 'tile W=1 ux=1 ur=4 nt=3 bx=4 n0=4 back=0 rows=16777216 nrd=1 blocks=65536',
+                   "fetch": 2146529859, "write": 70451615},
+    ('pack', 8): {"plan": 'tile W=2 ux=1 ur=4 nt=3 bx=4 n0=4 back=0 rows=8388608 nrd=1 blocks=32768',
+                   "fetch": 1073282649, "write": 67049141},
+    ('pack', 16): {"plan": 'tile W=4 ux=1 ur=4 nt=3 bx=4 n0=4 back=0 rows=4194304 nrd=1 blocks=16384',
+                   "fetch": 536656102, "write": 67074079},
+    ('pack', 32): {"plan": 'tile W=4 ux=1 ur=4 nt=3 bx=8 n0=8 back=0 rows=2097152 nrd=1 blocks=16384',
+                   "fetch": 268343084, "write": 67074974},
+    ('pack', 64): {"plan": 'tile W=16 ux=1 ur=4 nt=3 bx=4 n0=4 back=0 rows=1048576 nrd=1 blocks=4096',
+                   "fetch": 134188302, "write": 67127663},
+    ('pack', 128): {"plan": 'tile W=16 ux=1 ur=4 nt=3 bx=8 n0=8 back=0 rows=524288 nrd=1 blocks=4096',
+                   "fetch": 67110143, "write": 67101702},
+    ('pack', 256): {"plan": 'tile W=16 ux=1 ur=4 nt=3 bx=16 n0=16 back=0 rows=262144 nrd=1 blocks=4096',
+                   "fetch": 67110015, "write": 67110015},
+    ('pack', 512): {"plan": 'tile W=16 ux=4 ur=1 nt=3 bx=256 n0=4194304 back=0 rows=1 nrd=0 blocks=4096',
+                   "fetch": 67108864, "write": 67108864},
+    ('unpack', 1): {"plan": '4 x [prefetch bytes=16777216 tile=256 blocks=65536 grid=2048] + 4 x [tile W=1 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=16777216 nrd=1 blocks=65536 grid=256]',
+                   "fetch": 134391726, "write": 2145572518},
+    ('unpack', 2): {"plan": '4 x [prefetch bytes=16777216 tile=512 blocks=32768 grid=2048] + 4 x [tile W=2 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=8388608 nrd=1 blocks=32768 grid=256]',
+                   "fetch": 134391726, "write": 1072786259},
+    ('unpack', 4): {"plan": '4 x [prefetch bytes=16777216 tile=1024 blocks=16384 grid=2048] + 4 x [tile W=4 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=4194304 nrd=1 blocks=16384 grid=256]',
+                   "fetch": 134391726, "write": 536393130},
+    ('unpack', 8): {"plan": '4 x [prefetch bytes=16777216 tile=2048 blocks=8192 grid=2048] + 4 x [tile W=8 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=2097152 nrd=1 blocks=8192 grid=256]',
+                   "fetch": 134391726, "write": 268196565},
+    ('unpack', 16): {"plan": '4 x [prefetch bytes=16777216 tile=4096 blocks=4096 grid=2048] + 4 x [tile W=16 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=1048576 nrd=1 blocks=4096 grid=256]',
+                   "fetch": 134334409, "write": 134098282},
+    ('unpack', 32): {"plan": 'tile W=4 ux=1 ur=1 nt=7 bx=8 n0=8 back=0 rows=2097152 nrd=1 blocks=65536',
+                   "fetch": 67102723, "write": 67049141},
+    ('unpack', 64): {"plan": 'tile W=8 ux=1 ur=1 nt=7 bx=8 n0=8 back=0 rows=1048576 nrd=1 blocks=32768',
+                   "fetch": 67096582, "write": 67049141},
+    ('unpack', 128): {"plan": 'tile W=16 ux=1 ur=4 nt=3 bx=8 n0=8 back=0 rows=524288 nrd=1 blocks=4096',
+                   "fetch": 67104898, "write": 67145056},
+    ('unpack', 256): {"plan": 'tile W=16 ux=1 ur=4 nt=3 bx=16 n0=16 back=0 rows=262144 nrd=1 blocks=4096',
+                   "fetch": 67104898, "write": 67122931},
+    ('unpack', 512): {"plan": 'tile W=16 ux=4 ur=1 nt=3 bx=256 n0=4194304 back=0 rows=1 nrd=0 blocks=4096',
+                   "fetch": 67100676, "write": 67123699},
 }
 
 
