@@ -123,7 +123,7 @@ MEASURED_TRAFFIC = {
 
 # what tp_set_override keys are reset to after a call that ran under its own overrides (--points ...@key=value)
 OVERRIDE_DEFAULTS = {"stage": -1, "unpack_rule": 1, "nt": -1, "word": 0, "ur": -1, "xpose": 1, "narrow_partial_rows": 1,
-                     "stage_bytes": 16 << 20, "stage_grid": 0}
+                     "stage_bytes": 16 << 20, "stage_grid": 0, "grid": 0}
 
 
 def kernel_name(plan_line: str, op: str) -> str:
@@ -162,7 +162,8 @@ def cpu_model_string() -> str:
 FINAL_KEYS = ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
               "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline")
 ROOFLINE_KEYS = ("bound", "kernel", "achieved", "peak", "unit", "frac", "avg_launch_us", "algorithmic_bytes_per_launch",
-                 "launches_per_call", "traffic", "traffic_rate_gbs", "limit")
+                 "launches_per_call", "traffic", "traffic_rate_gbs", "rows_per_ns", "copy_write_requests_per_ns",
+                 "frac_of_copy_request_rate", "limit")
 CPU_KEYS = ("value", "unit", "cores", "cpu_model", "kind", "single_thread_value", "sample")
 
 
@@ -275,6 +276,23 @@ def main(argv=None):
     t1 = time.perf_counter()
 
     step_s = (t1 - t0) / args.steps
+
+    # reference: a dense 1 GiB copy through the library (the 1D path), large enough for launch and event
+    # overhead to vanish; a dense copy leaves L2 as one 64-byte write request per 64 bytes
+    gib = 1 << 30
+    ref_src = [torch.empty(gib, dtype=torch.uint8, device=dev).fill_(i + 1) for i in range(2)]
+    ref_dst = torch.empty(gib, dtype=torch.uint8, device=dev)
+    ref_t = tp.type_from_recipe(W.contiguous(gib, W.BYTE))
+    ref_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(6)]
+    for j, (e0, e1) in enumerate(ref_ev):
+        e0.record(stream)
+        tp.pack_async(ref_src[j % 2], 1, ref_t, ref_dst, gib, 0, stream)
+        e1.record(stream)
+    torch.cuda.synchronize()
+    ref_us = sorted(e0.elapsed_time(e1) for e0, e1 in ref_ev[2:])[1] * 1e3
+    copy_1gib = {"us": round(ref_us, 1), "gbs": round(2 * gib / ref_us / 1e3, 1), "write_requests_per_ns": gib / 64 / ref_us / 1e3}
+    tp.type_free(ref_t)
+    del ref_src, ref_dst
     bytes_per_step = sum(2 * points[i]["packed_bytes"] for _, i, _ in calls)   # read + write
     value = bytes_per_step / step_s / 1e9
 
@@ -323,6 +341,16 @@ def main(argv=None):
     }
     if dominant["launches_per_call"] > 1:
         roofline["limit"] = "avg_launch_us, achieved and traffic are per call, all of its launches included"
+    if dominant["op"] == "unpack" and dominant["a"][0] < 64:
+        # Rows below 64 bytes cost one masked 32-byte write request each, so the call is bound by the write
+        # requests per second the memory path takes, not by bytes: compare its rows/ns with the 64-byte
+        # write requests/ns of a dense 1 GiB copy through the same library, timed in this same run.
+        rows = dominant["algorithmic_bytes"] // 2 // dominant["a"][0]
+        roofline["rows_per_ns"] = round(rows / dominant["avg_us"] / 1e3, 2)
+        roofline["copy_write_requests_per_ns"] = round(copy_1gib["write_requests_per_ns"], 2)
+        roofline["frac_of_copy_request_rate"] = round(roofline["rows_per_ns"] / copy_1gib["write_requests_per_ns"], 3)
+        roofline["limit"] = ("one masked 32-byte write request per row: bound by the write requests/s of the memory path "
+                             "(see frac_of_copy_request_rate), 1 useful byte of 32 per request; figures are per call, all launches included")
     if "hbm_traffic_fetch_write" in dominant:
         roofline["traffic"] = sum(dominant["hbm_traffic_fetch_write"])
         roofline["traffic_fetch_write"] = dominant["hbm_traffic_fetch_write"]
@@ -337,6 +365,7 @@ def main(argv=None):
                    "packed_bytes_per_point": args.packed_bytes, "points": len(points),
                    "overrides": args.override, "bytes_per_step": bytes_per_step, "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4)},
         "roofline": roofline,
+        "copy_1GiB": copy_1gib,
         "kernels": kernels,
     }
     if args.points:

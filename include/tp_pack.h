@@ -311,7 +311,9 @@ int tp_resource_stats(int kind, tp_resource_counts *out);
  *   "stage"         "-1" (automatic: from 2^19 rows), "0" (never) or "1" (wherever it applies): staged
  *                   unpack of rows of one word at 512-, 256- or 128-byte pitch (a read-only pass per chunk
  *                   of packed bytes, then the stores); "stage_bytes" 4096 .. 2^30: packed bytes per chunk
- *                   (default 16 MiB); "stage_grid" "0" (automatic) or the workgroups of such a launch
+ *                   (default 16 MiB); "stage_grid" "0" (automatic) or the workgroups of such a launch (up to 2^20)
+ *   "grid"          "0" (default: one workgroup per tile) or 1 .. 2^20: workgroups of every other row-by-row
+ *                   launch, each then taking every grid-th tile (for measurements)
  *   "max_rows_per_launch", "max_words_per_run"  1 .. 2^30: split limits (tests lower them to
  *                   exercise the multi-launch path on small inputs)
  * tp_last_plan: describes the kernel launches of the calling thread's most recent

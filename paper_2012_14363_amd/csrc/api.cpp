@@ -33,6 +33,7 @@ std::atomic<int> g_unpack_rule{1};
 std::atomic<int> g_stage{-1};
 std::atomic<int64_t> g_stage_bytes{int64_t{16} << 20};
 std::atomic<int> g_stage_grid{0};
+std::atomic<int> g_grid{0};
 std::atomic<bool> g_allow_xpose{true};
 std::atomic<int64_t> g_max_rows_per_launch{int64_t{1} << 30};
 std::atomic<int64_t> g_max_words_per_run{int64_t{1} << 30};
@@ -189,6 +190,7 @@ int plan_request(bool unpack, const TypeNode& node, const void* typed_buf, int64
     in.stage = g_stage.load(std::memory_order_relaxed);
     in.stage_bytes = g_stage_bytes.load(std::memory_order_relaxed);
     in.stage_grid = g_stage_grid.load(std::memory_order_relaxed);
+    in.grid = g_grid.load(std::memory_order_relaxed);
     in.allow_xpose = g_allow_xpose.load(std::memory_order_relaxed);
     in.max_word_log2 = g_max_word_log2.load(std::memory_order_relaxed);
     in.nt = g_nt.load(std::memory_order_relaxed);
@@ -533,6 +535,11 @@ int tp_set_override(const char* key, const char* value) {
     if (!std::strcmp(key, "stage_grid")) {
         if (v < 0 || v > (1ll << 20)) return kErrArg;
         g_stage_grid.store(static_cast<int>(v));
+        return kSuccess;
+    }
+    if (!std::strcmp(key, "grid")) {
+        if (v < 0 || v > (1ll << 20)) return kErrArg;
+        g_grid.store(static_cast<int>(v));
         return kSuccess;
     }
     if (!std::strcmp(key, "unpack_rule")) {

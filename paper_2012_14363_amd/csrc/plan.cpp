@@ -14,7 +14,10 @@ constexpr int64_t kPageBytes = 4096;  // rows at least this far apart each need 
 constexpr int64_t kLineBytes = 128;   // memory line: what a partial write is read-modify-written in
 constexpr int64_t kSoloRows = int64_t{1} << 20, kSoloBytes = int64_t{8} << 20;  // batch requests worth their own launch
 constexpr int64_t kStagedRows = int64_t{1} << 19;  // fewer rows do not repay the extra passes (2^18: 15.0 against 14.5 us; 2^19: 22 against 26)
-constexpr uint32_t kStagedGrid = 256;              // workgroups of a staged launch: one per compute unit
+// Workgroups of a staged launch: a multiple of the eight XCDs.  Measured on 64 MiB of rows at 512-byte pitch, us for
+// 96 / 128 / 160 / 192 / 224 / 256 / 320 workgroups: 1-byte rows 1766 / 1779 / 1777 / 1750 / 1779 / 1784 / 2097, 2-byte rows
+// 894 / 902 / 892 / 882 / 906 / 971 / -, 8-byte rows 244 / 249 / 243 / 241 / 246 / 259 / -: a flat optimum from 168 to 208.
+constexpr uint32_t kStagedGrid = 192;
 constexpr uint32_t kPrefetchGridFactor = 8;        // the read-only pass takes that many times more
 
 struct Dim {
@@ -430,7 +433,7 @@ int plan_launches(const PlanInput& in, std::vector<Launch>* out) {
     }
     if (in.nt >= 0) nt = in.nt;
     if (in.max_ur == 1 || in.max_ur == 4) ur_short = in.max_ur;
-    Splitter s{in, word_log2, run, out, ur_short, nt};
+    Splitter s{in, word_log2, run, out, ur_short, nt, in.grid > 0 ? static_cast<uint32_t>(in.grid) : 0u};
     s.split_runs(dims, typed, in.packed);
     return kSuccess;
 }

@@ -128,6 +128,7 @@ struct PlanInput {
     int stage = -1;          // override: staged unpack of tiny rows: -1 = planner's choice, 0 = never, 1 = wherever it applies
     int64_t stage_bytes = int64_t{16} << 20;  // override: packed bytes per staged chunk
     int stage_grid = 0;      // override: workgroups of a staged launch (0 = planner's choice)
+    int grid = 0;            // override: workgroups of every other row-by-row launch (0 = one per tile)
     int64_t max_rows_per_launch = int64_t{1} << 30;   // tests lower these to force splitting
     int64_t max_words_per_run = int64_t{1} << 30;
 };

@@ -400,7 +400,7 @@ def test_emulated_staged_unpack_of_tiny_rows():
     # left to itself the planner stages from 2^19 rows on (64 MiB of typed memory at 128-byte pitch)
     res = _emulate_roundtrip(vector(1 << 19, 1, 128, BYTE), 1)
     assert res["unpack_plan"].count("prefetch") == 1 and res["unpack_plan"].count("tile W=1 ux=1 ur=1 nt=6 ") == 4
-    assert " grid=256" in res["unpack_plan"] and "prefetch bytes=524288 tile=1024 blocks=512 grid=512" in res["unpack_plan"]
+    assert " grid=192" in res["unpack_plan"] and "prefetch bytes=524288 tile=1024 blocks=512 grid=512" in res["unpack_plan"]
     assert "prefetch" not in _emulate_roundtrip(vector((1 << 19) - 1, 1, 128, BYTE), 1)["unpack_plan"]
     # objects that abut fold into rows and are staged together; objects apart are an outer dimension
     res = _emulate_roundtrip(subarray((512, 512), (512, 4), (0, 0), "C", BYTE), 3, stage=1)
@@ -572,14 +572,14 @@ def test_override_keys_take_what_the_header_documents():
     documented = {
         "word": ["0", "1", "2", "4", "8", "16"], "check_buffers": ["0", "1"], "nt": ["0", "1", "2", "3", "6", "7", "-1"],
         "ur": ["1", "4", "-1"], "xpose": ["0", "1"], "narrow_partial_rows": ["0", "1"], "unpack_rule": ["0", "1"],
-        "stage": ["0", "1", "-1"], "stage_bytes": ["4096", str(1 << 30), str(16 << 20)], "stage_grid": ["256", "1", "0"],
+        "stage": ["0", "1", "-1"], "stage_bytes": ["4096", str(1 << 30), str(16 << 20)], "stage_grid": ["256", "1", "0"], "grid": ["192", str(1 << 20), "0"],
         "max_rows_per_launch": ["1", "1000", str(1 << 30)], "max_words_per_run": ["1", "77", str(1 << 30)],
     }
     for key, values in documented.items():
         for v in values:   # the last value of each list is the default
             assert L.tp_set_override(key.encode(), v.encode()) == tp.TP_SUCCESS, (key, v)
     refused = {"word": ["3", "32", "-1"], "nt": ["4", "5", "8", "-2", "x", "", "3 "], "ur": ["0", "2", "8"], "xpose": ["2"],
-               "stage": ["2", "-2"], "stage_bytes": ["4095", str((1 << 30) + 1)], "stage_grid": ["-1", str((1 << 20) + 1)],
+               "stage": ["2", "-2"], "stage_bytes": ["4095", str((1 << 30) + 1)], "stage_grid": ["-1", str((1 << 20) + 1)], "grid": ["-1", str((1 << 20) + 1)],
                "unpack_rule": ["2"], "check_buffers": ["-1"], "narrow_partial_rows": ["7"],
                "max_rows_per_launch": ["0", str((1 << 30) + 1)], "max_words_per_run": ["0"], "nope": ["1"],
                "word ": ["4"]}
