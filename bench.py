@@ -45,6 +45,7 @@ def parse_args(argv=None):
     ap.add_argument("--no-extras", action="store_true", help="skip the secondary measurements")
     ap.add_argument("--detail", default=os.path.join(ROOT, "gpurun_out", "bench_detail.json"),
                     help="file that receives the full result (per-point table, secondary workloads)")
+    ap.add_argument("--verbose", action="store_true", help="print the stage the run is in to stderr")
     ap.add_argument("--points", default="", metavar="OP:A0[@KEY=VALUE...],...",
                     help="run only these calls of the sweep in the step, in this order, e.g. pack:32,unpack:1,unpack:1@stage=0 "
                          "(profiling and ablation runs; a call's @overrides hold for that call only; the printed value "
@@ -79,45 +80,45 @@ def sector_bound_fraction(run: int, granule: int = 128) -> float:
 # fetched, bytes written.  A point whose plan differs today reports no traffic rather than a stale one.
 MEASURED_TRAFFIC = {
     ('pack', 1): {"plan": 'tile W=1 ux=1 ur=4 nt=3 bx=1 n0=1 back=0 rows=67108864 nrd=1 blocks=65536',
-                   "fetch": 8585919339, "write": 72456804},
+                   "fetch": 8585916908, "write": 72429112},
     ('pack', 2): {"plan": 'tile W=1 ux=1 ur=4 nt=3 bx=2 n0=2 back=0 rows=33554432 nrd=1 blocks=65536',
-                   "fetch": 4293031572, "write": 72045842},
+                   "fetch": 4293019034, "write": 72044646},
     ('pack', 4): {"plan": 'tile W=1 ux=1 ur=4 nt=3 bx=4 n0=4 back=0 rows=16777216 nrd=1 blocks=65536',
-                   "fetch": 2146529859, "write": 70451615},
+                   "fetch": 2146530243, "write": 70420976},
     ('pack', 8): {"plan": 'tile W=2 ux=1 ur=4 nt=3 bx=4 n0=4 back=0 rows=8388608 nrd=1 blocks=32768',
-                   "fetch": 1073282649, "write": 67049141},
+                   "fetch": 1073278299, "write": 67045053},
     ('pack', 16): {"plan": 'tile W=4 ux=1 ur=4 nt=3 bx=4 n0=4 back=0 rows=4194304 nrd=1 blocks=16384',
-                   "fetch": 536656102, "write": 67074079},
+                   "fetch": 536656485, "write": 67083416},
     ('pack', 32): {"plan": 'tile W=4 ux=1 ur=4 nt=3 bx=8 n0=8 back=0 rows=2097152 nrd=1 blocks=16384',
-                   "fetch": 268343084, "write": 67074974},
+                   "fetch": 268343084, "write": 67062956},
     ('pack', 64): {"plan": 'tile W=16 ux=1 ur=4 nt=3 bx=4 n0=4 back=0 rows=1048576 nrd=1 blocks=4096',
-                   "fetch": 134188302, "write": 67127663},
+                   "fetch": 134187918, "write": 67143391},
     ('pack', 128): {"plan": 'tile W=16 ux=1 ur=4 nt=3 bx=8 n0=8 back=0 rows=524288 nrd=1 blocks=4096',
-                   "fetch": 67110143, "write": 67101702},
+                   "fetch": 67110143, "write": 67115769},
     ('pack', 256): {"plan": 'tile W=16 ux=1 ur=4 nt=3 bx=16 n0=16 back=0 rows=262144 nrd=1 blocks=4096',
-                   "fetch": 67110015, "write": 67110015},
+                   "fetch": 67109888, "write": 67113595},
     ('pack', 512): {"plan": 'tile W=16 ux=4 ur=1 nt=3 bx=256 n0=4194304 back=0 rows=1 nrd=0 blocks=4096',
                    "fetch": 67108864, "write": 67108864},
-    ('unpack', 1): {"plan": '4 x [prefetch bytes=16777216 tile=256 blocks=65536 grid=2048] + 4 x [tile W=1 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=16777216 nrd=1 blocks=65536 grid=256]',
-                   "fetch": 134391726, "write": 2145572518},
-    ('unpack', 2): {"plan": '4 x [prefetch bytes=16777216 tile=512 blocks=32768 grid=2048] + 4 x [tile W=2 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=8388608 nrd=1 blocks=32768 grid=256]',
-                   "fetch": 134391726, "write": 1072786259},
-    ('unpack', 4): {"plan": '4 x [prefetch bytes=16777216 tile=1024 blocks=16384 grid=2048] + 4 x [tile W=4 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=4194304 nrd=1 blocks=16384 grid=256]',
-                   "fetch": 134391726, "write": 536393130},
-    ('unpack', 8): {"plan": '4 x [prefetch bytes=16777216 tile=2048 blocks=8192 grid=2048] + 4 x [tile W=8 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=2097152 nrd=1 blocks=8192 grid=256]',
-                   "fetch": 134391726, "write": 268196565},
-    ('unpack', 16): {"plan": '4 x [prefetch bytes=16777216 tile=4096 blocks=4096 grid=2048] + 4 x [tile W=16 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=1048576 nrd=1 blocks=4096 grid=256]',
-                   "fetch": 134334409, "write": 134098282},
+    ('unpack', 1): {"plan": '4 x [prefetch bytes=16777216 tile=256 blocks=65536 grid=1536] + 4 x [tile W=1 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=16777216 nrd=1 blocks=65536 grid=192]',
+                   "fetch": 134391726, "write": 2145441687},
+    ('unpack', 2): {"plan": '4 x [prefetch bytes=16777216 tile=512 blocks=32768 grid=1536] + 4 x [tile W=2 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=8388608 nrd=1 blocks=32768 grid=192]',
+                   "fetch": 134391726, "write": 1072720844},
+    ('unpack', 4): {"plan": '4 x [prefetch bytes=16777216 tile=1024 blocks=16384 grid=1536] + 4 x [tile W=4 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=4194304 nrd=1 blocks=16384 grid=192]',
+                   "fetch": 134391726, "write": 536360422},
+    ('unpack', 8): {"plan": '4 x [prefetch bytes=16777216 tile=2048 blocks=8192 grid=1536] + 4 x [tile W=8 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=2097152 nrd=1 blocks=8192 grid=192]',
+                   "fetch": 134391726, "write": 268180211},
+    ('unpack', 16): {"plan": '4 x [prefetch bytes=16777216 tile=4096 blocks=4096 grid=1536] + 4 x [tile W=16 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=1048576 nrd=1 blocks=4096 grid=192]',
+                   "fetch": 134334409, "write": 134090105},
     ('unpack', 32): {"plan": 'tile W=4 ux=1 ur=1 nt=7 bx=8 n0=8 back=0 rows=2097152 nrd=1 blocks=65536',
-                   "fetch": 67102723, "write": 67049141},
+                   "fetch": 67102723, "write": 67045053},
     ('unpack', 64): {"plan": 'tile W=8 ux=1 ur=1 nt=7 bx=8 n0=8 back=0 rows=1048576 nrd=1 blocks=32768',
-                   "fetch": 67096582, "write": 67049141},
+                   "fetch": 67096582, "write": 67045053},
     ('unpack', 128): {"plan": 'tile W=16 ux=1 ur=4 nt=3 bx=8 n0=8 back=0 rows=524288 nrd=1 blocks=4096',
-                   "fetch": 67104898, "write": 67145056},
+                   "fetch": 67104770, "write": 67144926},
     ('unpack', 256): {"plan": 'tile W=16 ux=1 ur=4 nt=3 bx=16 n0=16 back=0 rows=262144 nrd=1 blocks=4096',
-                   "fetch": 67104898, "write": 67122931},
+                   "fetch": 67104898, "write": 67110910},
     ('unpack', 512): {"plan": 'tile W=16 ux=4 ur=1 nt=3 bx=256 n0=4194304 back=0 rows=1 nrd=0 blocks=4096',
-                   "fetch": 67100676, "write": 67123699},
+                   "fetch": 67100676, "write": 67120117},
 }
 
 
@@ -194,6 +195,10 @@ def main(argv=None):
     from paper_2012_14363_amd import binding as tp
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    def stage(text):
+        if args.verbose:
+            print(f"bench.py: {text}", file=sys.stderr, flush=True)
     if args.points:
         args.no_extras = True   # the secondary workloads live in the full arena
     tp.lib()
@@ -222,6 +227,7 @@ def main(argv=None):
     for i in used:
         bases[i] = total
         total += (points[i]["alloc_bytes"] + align - 1) // align * align
+    stage(f"filling {total >> 20} MiB of typed buffers")
     arena = W.fills.counter_bytes_torch(W.configs.SEED_BASE + 1, total, dev)
     packed = {i: torch.zeros(points[i]["packed_bytes"], dtype=torch.uint8, device=dev) for i in used}
     torch.cuda.synchronize()
@@ -253,8 +259,10 @@ def main(argv=None):
             if h >= 12:
                 tp.type_free(h)
 
+    stage("warm-up steps")
     for _ in range(args.warmup):
         run_step()
+    stage("plans")
     handles = {i: tp.type_from_recipe(points[i]["recipe"]) for i in used}
     if not args.points:
         for i in used:   # every unpack restores the bytes its pack took
@@ -269,6 +277,7 @@ def main(argv=None):
 
     all_events = [new_events() for _ in range(args.steps)]
     torch.cuda.synchronize()
+    stage("timed steps")
     t0 = time.perf_counter()
     for k in range(args.steps):
         run_step(all_events[k])
@@ -280,6 +289,7 @@ def main(argv=None):
     # reference: a dense 1 GiB copy through the library (the 1D path), large enough for launch and event
     # overhead to vanish; a dense copy leaves L2 as one 64-byte write request per 64 bytes
     gib = 1 << 30
+    stage("1 GiB reference copy")
     ref_src = [torch.empty(gib, dtype=torch.uint8, device=dev).fill_(i + 1) for i in range(2)]
     ref_dst = torch.empty(gib, dtype=torch.uint8, device=dev)
     ref_t = tp.type_from_recipe(W.contiguous(gib, W.BYTE))
@@ -293,6 +303,7 @@ def main(argv=None):
     copy_1gib = {"us": round(ref_us, 1), "gbs": round(2 * gib / ref_us / 1e3, 1), "write_requests_per_ns": gib / 64 / ref_us / 1e3}
     tp.type_free(ref_t)
     del ref_src, ref_dst
+    stage("results")
     bytes_per_step = sum(2 * points[i]["packed_bytes"] for _, i, _ in calls)   # read + write
     value = bytes_per_step / step_s / 1e9
 
