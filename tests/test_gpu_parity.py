@@ -203,7 +203,7 @@ def test_staged_unpack_of_tiny_rows(dev):
     # three row dimensions at 512-byte pitch, two objects apart
     say("staged unpack, 3D")
     plans = roundtrip(hvector(40, 1, 300 * 512 + 64, vector(300, 8, 512, BYTE)), 90, dev, typed_shift=4, position=3, seed=9)
-    assert plans["unpack"].count("prefetch") == 1 and " nrd=3 " in plans["unpack"] and " grid=256" in plans["unpack"], plans["unpack"]
+    assert plans["unpack"].count("prefetch") == 1 and " nrd=3 " in plans["unpack"] and " grid=192" in plans["unpack"], plans["unpack"]
     try:   # forced on a short message, with small chunks and few workgroups; and switched off
         tp.set_override("stage", 1)
         tp.set_override("stage_bytes", 8192)
