@@ -247,8 +247,10 @@ def main(argv=None):
             tp.set_override(key, OVERRIDE_DEFAULTS[key])
 
     def run_step(events=None):
-        handles = {i: tp.type_from_recipe(points[i]["recipe"]) for i in used}   # construct + commit
+        handles = {}
         for c, (op, i, ovr) in enumerate(calls):
+            if i not in handles:   # construct + commit, when the step first needs the type
+                handles[i] = tp.type_from_recipe(points[i]["recipe"])
             if events is not None:
                 events[c][0].record(stream)
             one_call(op, i, ovr, handles[i])
