@@ -63,7 +63,11 @@ extern "C" int tp_pack_host_static(const void* inbuf, int incount, tp_type t, vo
     // then one dense copy of exactly these bytes to the host buffer, both as kernels on the stream
     int64_t staged = 0;
     rc = transfer_with_device_buffer(false, inbuf, incount, t, staging, TP_STATIC_STAGING_BYTES, &staged, stream);
-    if (rc != kSuccess) return rc;
+    if (rc != kSuccess) {
+        // only a launch the runtime refused can fail after earlier launches of the call went out
+        if (rc == kErrOther) (void)hipStreamSynchronize(stream);
+        return rc;
+    }
     rc = copy_device_buffer_to_packed(staging, bytes, host_outbuf, outsize, *position, stream);
     if (rc != kSuccess) {
         (void)hipStreamSynchronize(stream);   // the gather may be in flight: leave the array quiet
