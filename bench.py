@@ -161,7 +161,7 @@ def cpu_model_string() -> str:
 
 
 FINAL_KEYS = ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
-              "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline")
+              "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline", "canonicalize_us_per_type")
 ROOFLINE_KEYS = ("bound", "kernel", "achieved", "peak", "unit", "frac", "avg_launch_us", "algorithmic_bytes_per_launch",
                  "launches_per_call", "traffic", "traffic_rate_gbs", "rows_per_ns", "copy_write_requests_per_ns",
                  "frac_of_copy_request_rate", "limit")
@@ -389,6 +389,12 @@ def main(argv=None):
     if not args.no_extras:
         out["extras"] = extras(W, tp, torch, np, dev, stream)
         out["other_workloads"] = other_workloads(W, tp, torch, arena, dev, stream)
+    # the metric's second half in the final line: commit (translate + canonicalize + StridedBlock) per type
+    rows = out.get("extras", {}).get("canonicalize_us_per_type")
+    if isinstance(rows, list) and rows:
+        commits = sorted(r["commit_us"] for r in rows)
+        out["canonicalize_us_per_type"] = {"median": commits[len(commits) // 2], "max": commits[-1], "types": len(rows),
+                                           "statistic": "trimean of 30000 commits per type"}
     try:
         os.makedirs(os.path.dirname(os.path.abspath(args.detail)), exist_ok=True)
         with open(args.detail, "w") as f:
