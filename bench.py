@@ -177,7 +177,18 @@ def final_line(out: dict) -> str:
     if "detail" in out:
         line["detail"] = out["detail"]
     text = json.dumps(line, separators=(",", ":"))
-    assert len(text) < 2000, len(text)
+    # never lose the line to its length: shorten the free-text fields first, then drop them
+    for cut in (160, 60, 0):
+        if len(text) < 2000:
+            break
+        for obj, key in ((line["roofline"], "limit"), (line.get("cpu_baseline", {}), "sample"), (line["config"], "overrides"),
+                         (line["config"], "only")):
+            if key in obj:
+                if cut and isinstance(obj[key], str):
+                    obj[key] = obj[key][:cut]
+                else:
+                    del obj[key]
+        text = json.dumps(line, separators=(",", ":"))
     return text
 
 

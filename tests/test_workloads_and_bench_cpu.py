@@ -102,6 +102,12 @@ def test_bench_final_line_is_compact_and_complete():
         assert key in got["cpu_baseline"], key
     assert "kernels" not in got and "extras" not in got and "other_workloads" not in got
     assert abs(got["roofline"]["frac"] - got["roofline"]["achieved"] / got["roofline"]["peak"]) < 1e-3
+    # free text far beyond anything the benchmark writes is shortened, never fatal
+    out["roofline"]["limit"] = "x" * 5000
+    out["cpu_baseline"]["sample"] = "s" * 5000
+    out["config"]["overrides"] = ["nt=3"] * 400
+    line = bench.final_line(out)
+    assert len(line) < 2000 and json.loads(line)["roofline"]["frac"] == 0.0095
 
 
 def test_bench_names_the_kernel_a_plan_line_runs():
