@@ -140,6 +140,22 @@ def test_random_medium_types(dev):
     assert {"tile W=1", "tile W=4", "tile W=16"} <= kinds
 
 
+def test_fewer_workgroups_than_tiles(dev):
+    # a launch of more tiles than a grid may have workgroups runs on fewer workgroups, each taking every
+    # gridDim-th tile; forced here with a handful of workgroups on launches of hundreds of tiles
+    try:
+        for grid in (1, 7, 64):
+            tp.set_override("grid", grid)
+            for t, incount in ((vector(20011, 3, 64, BYTE), 1), (vector(3001, 200, 512, BYTE), 2),
+                               (hvector(5, 1, 37 * 20480, hvector(37, 1, 20480, contiguous(4100, BYTE))), 1),
+                               (contiguous(3 << 20, BYTE), 1)):
+                say("grid", grid, "type", t[0], t[1])
+                plans = roundtrip(t, incount, dev, typed_shift=3, packed_shift=1, position=5, seed=grid)
+                assert f" grid={grid}" in plans["pack"] and f" grid={grid}" in plans["unpack"], plans
+    finally:
+        tp.set_override("grid", 0)
+
+
 @pytest.mark.parametrize("a0", [1, 2, 3, 4, 8, 16, 24, 48, 64, 200, 512, 1040, 4048, 4100, 4112, 20000])
 def test_tile_shapes_and_ragged_tails(dev, a0):
     say("tile shapes a0", a0)
