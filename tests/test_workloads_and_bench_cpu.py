@@ -123,3 +123,16 @@ def test_bench_names_the_kernel_a_plan_line_runs():
                             "tile W=1 ux=1 ur=1 nt=6 bx=1 n0=1 back=0 rows=16777216 nrd=1 blocks=65536 grid=256\n"
                             "prefetch bytes=16777216 tile=256 blocks=65536 grid=2048\n", "unpack") == \
         "prefetch_kernel + tile_kernel<0,1,1,true,1,6>"
+
+
+def test_bench_override_defaults_are_values_the_library_takes():
+    # bench.py puts a call's own overrides back to these after the call: each must be a key and value
+    # tp_set_override accepts, and the planner's own default for it
+    import bench
+    from paper_2012_14363_amd import binding as tp
+
+    for key, value in bench.OVERRIDE_DEFAULTS.items():
+        tp.set_override(key, value)
+    assert bench.OVERRIDE_DEFAULTS["stage_bytes"] == 16 << 20 and bench.OVERRIDE_DEFAULTS["stage"] == -1
+    args = bench.parse_args(["--points", "pack:32,unpack:1@stage=0@unpack_rule=0", "--steps", "3"])
+    assert args.points == "pack:32,unpack:1@stage=0@unpack_rule=0" and args.steps == 3 and args.gpus == 1
